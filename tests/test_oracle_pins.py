@@ -1,0 +1,300 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle (oracle/gemm_oracle.c) is the definition C = A B on unpacked int8.  It is
+pinned to things other than itself: the truth table the paper prints (Table I), the
+closed form of eq. (6), parity/bound invariants that follow from eq. (6)/(7), special
+cases with textbook answers, a library integer matmul, brute-force enumeration, and
+hand-worked 8-element vectors.  oracle/bitref.py (the paper's encodings and bit
+formulas) is pinned to the same table and to the oracle.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import bitref, oracle
+from paper_2205_09120_amd import synth
+
+
+def _table1(golden_dir):
+    rows = []
+    with open(f"{golden_dir}/table1_truth.txt") as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            tok = line.split()
+            rows.append([None if t == "-" else int(t) for t in tok])
+    assert len(rows) == 9
+    return rows
+
+
+# ---------------------------------------------------------------- Table I (paper, Section III-A)
+
+def test_table1_k1_products(golden_dir):
+    """A K=1 GEMM over every (x, y) pair must reproduce column z of Table I."""
+    rows = _table1(golden_dir)
+    xs = np.array([[r[0]] for r in rows], dtype=np.int8)          # 9 x 1
+    ys = np.array([[r[1] for r in rows]], dtype=np.int8)          # 1 x 9
+    C = oracle.gemm(xs, ys)
+    for i, r in enumerate(rows):
+        assert C[i, i] == r[2]
+
+
+def test_table1_encoding_and_formulas(golden_dir):
+    """Encodings (x+,x-), (y+,y-), y^b and the product bits z+, z-, u+, u- of Table I."""
+    for x, y, z, xp, xm, yp, ym, yb, zp, zm, up, um in _table1(golden_dir):
+        px = bitref.pack_ternary(np.array([[x]], dtype=np.int8))[0, 0]
+        py = bitref.pack_ternary(np.array([[y]], dtype=np.int8))[0, 0]
+        assert (int(px[0]), int(px[1])) == (xp, xm)
+        assert (int(py[0]), int(py[1])) == (yp, ym)
+        gzp = (xp & yp) | (xm & ym)
+        gzm = (xp & ym) | (xm & yp)
+        assert (gzp, gzm) == (zp, zm)
+        assert bitref.dot_tnn([xp], [xm], [yp], [ym]) == z
+        if yb is not None:
+            assert int(bitref.pack_binary(np.array([[y]], dtype=np.int8))[0, 0]) == yb
+            # one-bit evaluation of the ternary-binary formula (the word-wide version has 63 more pad bits)
+            nyb = 1 - yb
+            gup = (xp | yb) & (xm | nyb)
+            gum = (xp | nyb) & (xm | yb)
+            assert (gup & 1, gum & 1) == (up, um)
+            assert up - um == z
+
+
+def test_table2_kmax(golden_dir):
+    """eq. (4) read as floor((2^q-1)/(2^p-1)^2) reproduces the k_max column of Table II."""
+    with open(f"{golden_dir}/table2_kmax.txt") as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            algo, p, q, signed, kmax = line.split()
+            p, q, signed, kmax = int(p), int(q), int(signed), int(kmax)
+            qq = q - 1 if signed else q
+            assert (2 ** qq - 1) // (2 ** p - 1) ** 2 == kmax, algo
+
+
+# ---------------------------------------------------------------- hand-worked vectors (from the encodings of Section III-A)
+
+def test_hand_vectors():
+    a_b = np.array([[1, -1, 1, 1, -1, -1, 1, -1]], dtype=np.int8)
+    b_b = np.array([[1, 1, -1, 1, -1, 1, 1, 1]], dtype=np.int8)
+    assert int(bitref.pack_binary(a_b)[0, 0]) == 0xB2
+    assert int(bitref.pack_binary(b_b)[0, 0]) == 0x14
+    assert oracle.gemm(a_b, np.ascontiguousarray(b_b.T))[0, 0] == 0            # 8 - 2*popc(0xA6)
+
+    a_t = np.array([[1, 0, -1, 1, -1, 0, 1, -1]], dtype=np.int8)
+    b_t = np.array([[1, 1, -1, 0, 1, -1, -1, -1]], dtype=np.int8)
+    pa, pb = bitref.pack_ternary(a_t)[0, 0], bitref.pack_ternary(b_t)[0, 0]
+    assert (int(pa[0]), int(pa[1])) == (0x49, 0x94)
+    assert (int(pb[0]), int(pb[1])) == (0x13, 0xE4)
+    assert oracle.gemm(a_t, np.ascontiguousarray(b_t.T))[0, 0] == 1            # popc(0x85) - popc(0x50)
+    assert bitref.dot_tnn([0x49], [0x94], [0x13], [0xE4]) == 1
+
+    assert oracle.gemm(a_t, np.ascontiguousarray(b_b.T))[0, 0] == 4            # ternary a, binary y
+    assert bitref.dot_tbn([0x49], [0x94], [0x14]) == 4
+
+
+# ---------------------------------------------------------------- closed form eq. (6), invariants from eq. (6)/(7)
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_bnn_closed_form_and_invariants(seed):
+    A, B = synth.make_custom("bnn", 17, 23, 131, seed)
+    C = oracle.gemm(A, B)
+    ham = ((A[:, :, None] < 0) != (B[None, :, :] < 0)).sum(axis=1)             # Hamming distance of the sign bits
+    assert np.array_equal(C, 131 - 2 * ham)
+    assert np.all(np.abs(C) <= 131) and np.all((C - 131) % 2 == 0)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_tnn_invariants(seed):
+    A, B = synth.make_custom("tnn", 19, 21, 200, seed)
+    C = oracle.gemm(A, B)
+    n11 = ((A != 0).astype(np.int32) @ (B != 0).astype(np.int32))
+    assert np.all(np.abs(C) <= n11) and np.all((C - n11) % 2 == 0)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_tbn_invariants(seed):
+    A, B = synth.make_custom("tbn", 19, 21, 200, seed)
+    C = oracle.gemm(A, B)
+    nnz = (A != 0).sum(axis=1, keepdims=True)
+    assert np.all(np.abs(C) <= nnz) and np.all((C - nnz) % 2 == 0)
+
+
+# ---------------------------------------------------------------- special cases with known answers
+
+def test_special_cases():
+    A, B = synth.make_custom("tnn", 12, 15, 77, 5)
+    ones = np.ones_like(A)
+    assert np.array_equal(oracle.gemm(ones, B), np.broadcast_to(B.sum(axis=0, dtype=np.int32), (12, 15)))
+    assert np.array_equal(oracle.gemm(-A, B), -oracle.gemm(A, B))
+    assert not oracle.gemm(np.zeros_like(A), B).any()
+    G = oracle.gemm(A, np.ascontiguousarray(A.T))                              # Gram matrix
+    assert np.array_equal(G, G.T) and np.array_equal(np.diag(G), (A != 0).sum(axis=1))
+    Ab, _ = synth.make_custom("bnn", 9, 9, 65, 6)
+    Gb = oracle.gemm(Ab, np.ascontiguousarray(Ab.T))
+    assert np.array_equal(np.diag(Gb), np.full(9, 65))
+    # identity on the depth axis picks rows of B
+    I = np.eye(15, dtype=np.int8)
+    assert np.array_equal(oracle.gemm(I, np.ascontiguousarray(B[:15])), B[:15].astype(np.int32))
+    # a non-square, non-symmetric hand case catches a transposed operand
+    A2 = np.array([[1, -1, 0], [0, 1, 1]], dtype=np.int8)
+    B2 = np.array([[1, 0], [-1, 1], [1, -1]], dtype=np.int8)
+    assert oracle.gemm(A2, B2).tolist() == [[2, -1], [0, 0]]
+
+
+def test_depth_64_vs_65():
+    """Appending one depth position changes C by exactly that position's products."""
+    A, B = synth.make_custom("tnn", 5, 7, 65, 8)
+    C64 = oracle.gemm(np.ascontiguousarray(A[:, :64]), np.ascontiguousarray(B[:64]))
+    C65 = oracle.gemm(A, B)
+    assert np.array_equal(C65 - C64, A[:, 64:65].astype(np.int32) * B[64:65].astype(np.int32))
+
+
+# ---------------------------------------------------------------- library routine and brute force
+
+@pytest.mark.parametrize("kind,shape", [("tnn", (33, 47, 129)), ("tbn", (64, 10, 300)), ("bnn", (7, 130, 64))])
+def test_against_numpy_matmul(kind, shape):
+    A, B = synth.make_custom(kind, *shape, seed=11)
+    assert np.array_equal(oracle.gemm(A, B), A.astype(np.int64) @ B.astype(np.int64))
+
+
+def test_brute_force_tiny():
+    """Every legal pair of ternary vectors of depth <= 3 (3^K * 3^K cases), by direct evaluation."""
+    for K in (1, 2, 3):
+        vecs = list(itertools.product((-1, 0, 1), repeat=K))
+        A = np.array(vecs, dtype=np.int8)                        # 3^K x K
+        B = np.ascontiguousarray(A.T)                            # K x 3^K
+        C = oracle.gemm(A, B)
+        for i, a in enumerate(vecs):
+            for j, b in enumerate(vecs):
+                assert C[i, j] == sum(x * y for x, y in zip(a, b))
+
+
+def test_samples_entry_matches_full():
+    A, B = synth.make_custom("tnn", 40, 50, 333, 3)
+    C = oracle.gemm(A, B)
+    rng = np.random.default_rng(0)
+    ii, jj = rng.integers(0, 40, 200), rng.integers(0, 50, 200)
+    assert np.array_equal(oracle.gemm_samples(A, B, ii, jj), C[ii, jj])
+    # and the sampler itself against a python sum
+    for s in range(5):
+        assert oracle.gemm_samples(A, B, ii[s:s + 1], jj[s:s + 1])[0] == sum(
+            int(A[ii[s], t]) * int(B[t, jj[s]]) for t in range(333))
+
+
+def test_thread_count_does_not_change_result():
+    A, B = synth.make_custom("tbn", 31, 29, 190, 4)
+    assert np.array_equal(oracle.gemm(A, B, threads=1), oracle.gemm(A, B, threads=4))
+
+
+def test_empty():
+    A = np.zeros((0, 5), dtype=np.int8)
+    B = np.zeros((5, 3), dtype=np.int8)
+    assert oracle.gemm(A, B).shape == (0, 3)
+    A = np.zeros((2, 0), dtype=np.int8)
+    B = np.zeros((0, 3), dtype=np.int8)
+    assert not oracle.gemm(A, B).any()
+
+
+# ---------------------------------------------------------------- the bit-formula evaluator and the reference packer
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+@pytest.mark.parametrize("K", [1, 63, 64, 65, 130])
+def test_bitwise_formulas_equal_definition(kind, K):
+    A, B = synth.make_custom(kind, 6, 5, K, seed=K)
+    assert np.array_equal(bitref.gemm_bitwise(kind, A, B), oracle.gemm(A, B))
+
+
+def test_ref_packer_bit_by_bit_and_roundtrip():
+    X, _ = synth.make_custom("tnn", 5, 1, 150, 9)
+    P = bitref.pack_ternary(X)
+    assert P.shape == (5, 3, 2) and P.dtype == np.uint64
+    for r in range(5):
+        for w in range(3):
+            plus = minus = 0
+            for b in range(64):
+                k = 64 * w + b
+                if k < 150:
+                    plus |= int(X[r, k] > 0) << b
+                    minus |= int(X[r, k] < 0) << b
+            assert int(P[r, w, 0]) == plus and int(P[r, w, 1]) == minus
+    assert np.array_equal(bitref.unpack_ternary(P, 150), X)
+    Xb, _ = synth.make_custom("bnn", 4, 1, 70, 10)
+    Pb = bitref.pack_binary(Xb)
+    for r in range(4):
+        for w in range(2):
+            word = 0
+            for b in range(64):
+                k = 64 * w + b
+                if k < 70:
+                    word |= int(Xb[r, k] < 0) << b
+            assert int(Pb[r, w]) == word
+    assert np.array_equal(bitref.unpack_binary(Pb, 70), Xb)
+
+
+# ---------------------------------------------------------------- planted mistakes must be caught by the pins
+
+def _pins(gemm, golden_dir):
+    """A subset of the pins above as one function of the gemm callable; raises on the first failure."""
+    rows = _table1(golden_dir)
+    xs = np.array([[r[0]] for r in rows], dtype=np.int8)
+    ys = np.array([[r[1] for r in rows]], dtype=np.int8)
+    C = gemm(xs, ys)
+    assert all(C[i, i] == r[2] for i, r in enumerate(rows))
+    A2 = np.array([[1, -1, 0], [0, 1, 1]], dtype=np.int8)
+    B2 = np.array([[1, 0], [-1, 1], [1, -1]], dtype=np.int8)
+    assert gemm(A2, B2).tolist() == [[2, -1], [0, 0]]
+    Ab, Bb = synth.make_custom("bnn", 9, 11, 300, 1)
+    ham = ((Ab[:, :, None] < 0) != (Bb[None, :, :] < 0)).sum(axis=1)
+    assert np.array_equal(gemm(Ab, Bb), 300 - 2 * ham)
+    ones = np.ones((4, 300), dtype=np.int8)
+    assert np.array_equal(gemm(ones, Bb), np.broadcast_to(Bb.sum(axis=0, dtype=np.int32), (4, 11)))
+    # square, non-symmetric: catches a transposed operand that shape checks cannot
+    As, Bs = synth.make_custom("tnn", 6, 6, 6, 2)
+    want = [[sum(int(As[i, t]) * int(Bs[t, j]) for t in range(6)) for j in range(6)] for i in range(6)]
+    assert gemm(As, Bs).tolist() == want
+
+
+def test_pins_pass_for_the_oracle(golden_dir):
+    _pins(oracle.gemm, golden_dir)
+
+
+@pytest.mark.parametrize("mutant", ["wrong_sign", "dropped_last_term", "skipped_first_term", "transposed_b",
+                                    "int8_accumulator", "abs_product"])
+def test_pins_catch_planted_mistakes(mutant, golden_dir):
+    """Plausible wrong oracles, planted on the CPU, each fail at least one pin."""
+    def wrong(A, B):
+        a, b = A.astype(np.int64), B.astype(np.int64)
+        if mutant == "wrong_sign":
+            return (-(a @ b)).astype(np.int32)
+        if mutant == "dropped_last_term":
+            return (a[:, :-1] @ b[:-1]).astype(np.int32)
+        if mutant == "skipped_first_term":
+            return (a[:, 1:] @ b[1:]).astype(np.int32)
+        if mutant == "transposed_b":
+            return (a @ b.T).astype(np.int32) if b.shape[0] == b.shape[1] else (a @ b).astype(np.int32)
+        if mutant == "int8_accumulator":
+            return (a @ b).astype(np.int8).astype(np.int32)
+        if mutant == "abs_product":
+            return (np.abs(a) @ np.abs(b)).astype(np.int32)
+        raise AssertionError(mutant)
+    with pytest.raises(AssertionError):
+        _pins(wrong, golden_dir)
+
+
+# ---------------------------------------------------------------- generator sanity (not parity)
+
+def test_generator_statistics():
+    w = synth.WORKLOADS["cfg1_tnn_conv3x3x64_16x16"]
+    A, B = synth.make_inputs(w)
+    assert A.shape == (64, 576) and B.shape == (576, 256) and A.dtype == np.int8
+    assert set(np.unique(A)) == {-1, 0, 1}
+    assert abs((A == 0).mean() - 0.3) < 0.02 and abs((A == 1).mean() - 0.35) < 0.02
+    C = oracle.gemm(A, B)
+    assert abs(C.std() - np.sqrt(576 * 0.49)) < 1.0
+    A2, B2 = synth.make_inputs(w)
+    assert np.array_equal(A, A2) and np.array_equal(B, B2)
+    wb = synth.WORKLOADS["cfg2_bnn_conv3x3x128_56x56"]
+    Ab, _ = synth.make_inputs(wb)
+    assert set(np.unique(Ab)) == {-1, 1} and abs((Ab == 1).mean() - 0.5) < 0.01
