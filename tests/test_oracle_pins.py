@@ -250,6 +250,7 @@ def _pins(gemm, golden_dir):
     assert np.array_equal(gemm(Ab, Bb), 300 - 2 * ham)
     ones = np.ones((4, 300), dtype=np.int8)
     assert np.array_equal(gemm(ones, Bb), np.broadcast_to(Bb.sum(axis=0, dtype=np.int32), (4, 11)))
+    assert np.array_equal(gemm(ones, np.ascontiguousarray(-ones.T)), np.full((4, 4), -300))   # needs > 8/16-bit-free range
     # square, non-symmetric: catches a transposed operand that shape checks cannot
     As, Bs = synth.make_custom("tnn", 6, 6, 6, 2)
     want = [[sum(int(As[i, t]) * int(Bs[t, j]) for t in range(6)) for j in range(6)] for i in range(6)]
