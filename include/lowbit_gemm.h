@@ -1,0 +1,137 @@
+/*
+ * lowbit_gemm.h -- C ABI of the MI355X (gfx950) low-bit matrix multiplication library.
+ *
+ * The library computes C = A B (A: M x K, B: K x N, C: M x N, the "height", "width" and
+ * "depth" of Section II-A of the paper) for the three operand classes of Section III:
+ *     BNN  A, B in {-1,+1}
+ *     TNN  A, B in {-1,0,+1}
+ *     TBN  A in {-1,0,+1}, B in {-1,+1}
+ * on bit-packed operands (Section III-A): a binary value is one bit (+1 -> 0, -1 -> 1), a
+ * ternary value two bits (x+, x-) with +1 -> (1,0), 0 -> (0,0), -1 -> (0,1); the product is
+ * obtained with AND/OR/XOR and population counts (eq. (6) and (7)).  Results are exact.
+ * The paper accumulates in signed 16-bit lanes (k_max = 32767, Section IV-A); this library
+ * accumulates and stores 32-bit integers, which gives the same values for every K the paper
+ * allows and lifts the depth limit to 2^31 - 1.
+ *
+ * General rules for every entry point
+ *   - Every pointer argument is a DEVICE pointer on the current HIP device, owned by the
+ *     caller, and must stay valid until the work queued on `stream` has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: they do not synchronize, do not allocate and do not free.
+ *   - Return value: LB_OK (0) or a negative lb_status.  On failure nothing was enqueued
+ *     (except LB_EHIP, where the runtime refused a launch) and lb_last_error() returns a
+ *     message for the calling thread.
+ *   - Pointers must be aligned to 16 bytes (packed operands, int8 sources) or 4 bytes (C).
+ *
+ * Packed operand format (version LB_FORMAT_VERSION)
+ *   A matrix is packed as `rows` bit strings along the depth k; KW = ceil(K/64).
+ *   Word w of a bit string holds depth positions 64w .. 64w+63, position k in bit (k mod 64)
+ *   counted from the least significant bit.  Little-endian uint64_t.
+ *     binary :  dst[r*KW + w]
+ *     ternary:  dst[(r*KW + w)*2 + 0] = plus plane (x+),  dst[(r*KW + w)*2 + 1] = minus plane (x-)
+ *   Positions k >= K in the last word are 0 in every plane.
+ *   For A (M x K) the bit strings are its rows; for B (K x N) they are its columns.
+ */
+#ifndef LOWBIT_GEMM_H
+#define LOWBIT_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LB_FORMAT_VERSION 1
+
+#if defined(__GNUC__)
+#define LB_API __attribute__((visibility("default")))
+#else
+#define LB_API
+#endif
+
+typedef enum lb_status {
+    LB_OK = 0,
+    LB_EINVAL = -1,       /* null pointer, non-positive dimension, bad stride / leading dimension, misaligned pointer */
+    LB_EOVERFLOW = -2,    /* a size does not fit the index arithmetic (K > 2^31-1, rows*KW too large, ...) */
+    LB_EHIP = -3,         /* the HIP runtime reported an error at launch; message holds hipGetErrorString */
+    LB_EUNSUPPORTED = -4  /* valid request that this build cannot serve (e.g. device is not gfx950) */
+} lb_status;
+
+/* Message describing the last failure on the calling thread ("" if none).  Host pointer, owned by the library. */
+LB_API const char *lb_last_error(void);
+
+/* LB_FORMAT_VERSION the library was built with. */
+LB_API int lb_format_version(void);
+
+/* Bytes of a packed operand of `rows` bit strings of depth K: rows*ceil(K/64)*8 (binary) or *16 (ternary).
+ * Returns 0 when rows < 0, K < 0 or the size overflows size_t. */
+LB_API size_t packed_binary_bytes(int64_t rows, int64_t K);
+LB_API size_t packed_ternary_bytes(int64_t rows, int64_t K);
+
+/*
+ * pack_binary / pack_ternary -- encode an int8 matrix into the packed format (Section III-A encodings;
+ * they take the place of the paper's PackNRowsA / PackNColsB reorder step of Algorithms 1 and 2).
+ *
+ *   src       device, int8.  Element (r, k) of the `rows` x K logical matrix is src[r*stride_r + k*stride_k].
+ *             A (M x K row-major): rows = M, stride_r = lda (>= K), stride_k = 1.
+ *             B (K x N row-major): rows = N, stride_r = 1, stride_k = ldb (>= N).
+ *             One of the two strides must be 1 and the other >= the extent it strides over.
+ *   dst       device, packed_*_bytes(rows, K) bytes, overwritten completely (pad bits included).
+ *   Encoding  binary:  x < 0 -> bit 1, otherwise bit 0.
+ *             ternary: x > 0 -> (1,0), x < 0 -> (0,1), x == 0 -> (0,0).  The code (1,1) is never produced.
+ *             Inputs outside the legal value sets are encoded by sign as above; no error is raised.
+ * rows == 0 or K == 0 is a valid no-op.
+ */
+LB_API int pack_binary(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint64_t *dst,
+                void *stream);
+LB_API int pack_ternary(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint64_t *dst,
+                 void *stream);
+
+/*
+ * gemm_bnn -- binary x binary, eq. (6):  C[i][j] = K - 2 * sum_w popcount(Ap[i][w] xor Bp[j][w]).
+ * gemm_tnn -- ternary x ternary, eq. (7) with the ternary product of Section III-A (Table I, columns z+, z-).
+ * gemm_tbn -- ternary A x binary B, eq. (7) with the ternary-binary product (Table I, columns u+, u-).
+ *
+ *   Ap        device, packed A: M bit strings of depth K (binary for gemm_bnn, ternary otherwise).
+ *   Bp        device, packed B: N bit strings (the columns of B) of depth K (ternary for gemm_tnn, binary otherwise).
+ *   C         device, int32, row-major M x N with leading dimension ldc >= N; overwritten (no accumulation into C).
+ *   K         true depth (pad bits of the last word must be 0 as pack_* writes them); 1 <= K <= 2^31 - 1.
+ * The kernels evaluate algebraically equivalent forms of the paper's bit formulas (see the kernel sources);
+ * the integers written are identical.  Packed operands holding the invalid ternary code (1,1) give undefined C.
+ * M == 0 or N == 0 is a valid no-op; K == 0 is LB_EINVAL.
+ */
+LB_API int gemm_bnn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream);
+LB_API int gemm_tnn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream);
+LB_API int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream);
+
+/*
+ * gemm_i8_mfma -- the same product C = A B from UNPACKED int8 operands with int32 accumulation on the
+ * integer matrix cores.  It plays the role the 8-bit gemmlowp multiplication (U8, Section IV, Table II/III)
+ * plays in the paper: the comparison point for the low-bit kernels.  Any int8 values are allowed.
+ *   A  device, int8 row-major M x K, leading dimension lda >= K
+ *   B  device, int8 row-major K x N, leading dimension ldb >= N
+ *   C  device, int32 row-major M x N, leading dimension ldc >= N; overwritten.
+ */
+LB_API int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                 int32_t *C, int64_t ldc, void *stream);
+
+/*
+ * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
+ *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn
+ *   variant  index into that op's variant table, or -1 to restore shape-based selection.
+ * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
+ * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).
+ * Process-wide; not meant to be changed while other threads are inside gemm_* calls.
+ */
+LB_API int lb_set_variant(int op, int variant);
+LB_API int lb_num_variants(int op);
+LB_API const char *lb_variant_name(int op, int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOWBIT_GEMM_H */

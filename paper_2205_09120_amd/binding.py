@@ -1,0 +1,184 @@
+"""ctypes binding of liblowbit_gemm.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors; torch provides device memory and the stream, nothing else.  Every
+function raises LowbitError when the library returns a status other than LB_OK, and RuntimeError when the
+library is missing: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblowbit_gemm.so")
+
+LB_OK, LB_EINVAL, LB_EOVERFLOW, LB_EHIP, LB_EUNSUPPORTED = 0, -1, -2, -3, -4
+OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
+_OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
+
+EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
+           "pack_ternary", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_i8_mfma", "lb_set_variant", "lb_num_variants",
+           "lb_variant_name")
+
+
+class LowbitError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"lowbit_gemm status {status}: {message}")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2205_09120_amd.build` "
+                               "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.lb_last_error.restype = ctypes.c_char_p
+        L.lb_last_error.argtypes = []
+        L.lb_format_version.restype = ci
+        L.lb_format_version.argtypes = []
+        for f in (L.packed_binary_bytes, L.packed_ternary_bytes):
+            f.restype = ctypes.c_size_t
+            f.argtypes = [i64, i64]
+        for f in (L.pack_binary, L.pack_ternary):
+            f.restype = ci
+            f.argtypes = [vp, i64, i64, i64, i64, vp, vp]
+        for f in (L.gemm_bnn, L.gemm_tnn, L.gemm_tbn):
+            f.restype = ci
+            f.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
+        L.gemm_i8_mfma.restype = ci
+        L.gemm_i8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.lb_set_variant.restype = ci
+        L.lb_set_variant.argtypes = [ci, ci]
+        L.lb_num_variants.restype = ci
+        L.lb_num_variants.argtypes = [ci]
+        L.lb_variant_name.restype = ctypes.c_char_p
+        L.lb_variant_name.argtypes = [ci, ci]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != LB_OK:
+        raise LowbitError(status, lib().lb_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def lb_last_error() -> str:
+    return lib().lb_last_error().decode()
+
+
+def lb_format_version() -> int:
+    return lib().lb_format_version()
+
+
+def packed_binary_bytes(rows: int, K: int) -> int:
+    return lib().packed_binary_bytes(rows, K)
+
+
+def packed_ternary_bytes(rows: int, K: int) -> int:
+    return lib().packed_ternary_bytes(rows, K)
+
+
+def _pack(fn, nbytes_fn, src, rows, K, stride_r, stride_k, dst, stream):
+    if dst is None:
+        dst = torch.empty(max(nbytes_fn(rows, K) // 8, 0), dtype=torch.int64, device=src.device)
+    _check(fn(_ptr(src), rows, K, stride_r, stride_k, _ptr(dst), _stream(stream)))
+    return dst
+
+
+def pack_binary(src: torch.Tensor, rows: int, K: int, stride_r: int, stride_k: int,
+                dst: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Element (r,k) = src.flatten()[r*stride_r + k*stride_k].  Returns dst (int64 words, rows*ceil(K/64))."""
+    return _pack(lib().pack_binary, packed_binary_bytes, src, rows, K, stride_r, stride_k, dst, stream)
+
+
+def pack_ternary(src: torch.Tensor, rows: int, K: int, stride_r: int, stride_k: int,
+                 dst: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Returns dst (int64 words, rows*ceil(K/64)*2: plus word, minus word, ...)."""
+    return _pack(lib().pack_ternary, packed_ternary_bytes, src, rows, K, stride_r, stride_k, dst, stream)
+
+
+def _gemm(fn, M, N, K, Ap, Bp, C, ldc, stream):
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int32, device=Ap.device)
+        ldc = N
+    elif ldc is None:
+        ldc = C.stride(0) if C.dim() == 2 else N
+    _check(fn(M, N, K, _ptr(Ap), _ptr(Bp), _ptr(C), ldc, _stream(stream)))
+    return C
+
+
+def gemm_bnn(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    return _gemm(lib().gemm_bnn, M, N, K, Ap, Bp, C, ldc, stream)
+
+
+def gemm_tnn(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    return _gemm(lib().gemm_tnn, M, N, K, Ap, Bp, C, ldc, stream)
+
+
+def gemm_tbn(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    return _gemm(lib().gemm_tbn, M, N, K, Ap, Bp, C, ldc, stream)
+
+
+def gemm_i8_mfma(M, N, K, A, lda, B, ldb, C=None, ldc=None, stream=None):
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int32, device=A.device)
+        ldc = N
+    elif ldc is None:
+        ldc = C.stride(0)
+    _check(lib().gemm_i8_mfma(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream)))
+    return C
+
+
+def lb_set_variant(op, variant: int) -> None:
+    _check(lib().lb_set_variant(_OPS.get(op, op), variant))
+
+
+def lb_num_variants(op) -> int:
+    return lib().lb_num_variants(_OPS.get(op, op))
+
+
+def lb_variant_name(op, variant: int) -> Optional[str]:
+    s = lib().lb_variant_name(_OPS.get(op, op), variant)
+    return None if s is None else s.decode()
+
+
+# ------------------------------------------------------------------ conveniences built only from the calls above
+
+def pack_a(kind: str, A: torch.Tensor, stream=None) -> torch.Tensor:
+    """Pack the left matrix A (M x K, row-major int8) for gemm_<kind>: ternary for tnn/tbn, binary for bnn."""
+    M, K = A.shape
+    assert A.dtype == torch.int8 and A.stride(1) == 1
+    f = pack_binary if kind == "bnn" else pack_ternary
+    return f(A, M, K, A.stride(0), 1, stream=stream)
+
+
+def pack_b(kind: str, B: torch.Tensor, stream=None) -> torch.Tensor:
+    """Pack the right matrix B (K x N, row-major int8) along its columns: ternary for tnn, binary otherwise."""
+    K, N = B.shape
+    assert B.dtype == torch.int8 and B.stride(1) == 1
+    f = pack_ternary if kind == "tnn" else pack_binary
+    return f(B, N, K, 1, B.stride(0), stream=stream)
+
+
+def gemm(kind: str, M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    return {"bnn": gemm_bnn, "tnn": gemm_tnn, "tbn": gemm_tbn}[kind](M, N, K, Ap, Bp, C, ldc, stream)

@@ -1,0 +1,261 @@
+// C ABI of the library: argument validation, shape-based kernel selection, error reporting.
+// Every check runs before the first HIP call, so invalid requests can be rejected on a machine without a GPU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/lowbit_gemm.h"
+#include "lowbit_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+int g_forced[3] = {-1, -1, -1};
+
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K must fit
+constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
+
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// rows*ceil(K/64)*unit with overflow detection; 0 on failure
+size_t packed_bytes(int64_t rows, int64_t K, int64_t unit)
+{
+    if (rows < 0 || K < 0)
+        return 0;
+    const int64_t KW = K / 64 + (K % 64 != 0);
+    if (rows == 0 || KW == 0)
+        return 0;
+    if (KW > INT64_MAX / unit || rows > INT64_MAX / (KW * unit))
+        return 0;
+    return (size_t)(rows * KW * unit);
+}
+
+int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r,
+            int64_t stride_k, uint64_t *dst, void *stream)
+{
+    if (rows < 0 || K < 0)
+        return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
+    if (rows == 0 || K == 0)
+        return LB_OK;
+    if (!src || !dst)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (K > kMaxDepth || rows > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1", name, (long long)rows, (long long)K);
+    // a single bit string (rows == 1) or a single depth position (K == 1) makes the other stride irrelevant
+    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
+    const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
+    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
+        return fail(LB_EINVAL,
+                    "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
+                    "stride_k=%lld rows=%lld K=%lld)",
+                    name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
+    if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
+        return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
+    if (packed_bytes(rows, K, ternary ? 16 : 8) == 0)
+        return fail(LB_EOVERFLOW, "%s: packed size overflows", name);
+    if (!aligned(dst, 16))
+        return fail(LB_EINVAL, "%s: dst must be 16-byte aligned", name);
+    const hipError_t e =
+        lowbit::launch_pack(ternary, src, rows, K, stride_r, stride_k, dst, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+// Pick a tile variant: the largest workgroup tile that still yields enough workgroups to occupy the device
+// several times over; smaller problems fall through to smaller tiles.
+int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV)
+{
+    constexpr int64_t kWanted = 256 * 6;  // workgroups: compute units x a few rounds
+    int best = 0;
+    for (int i = 0; i < count; ++i) {
+        const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
+        if (wg >= kWanted)
+            best = i;  // tables are ordered by increasing tile size
+    }
+    return best;
+}
+
+int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
+            int32_t *C, int64_t ldc, void *stream)
+{
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    if (K > kMaxDepth)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 2^31-1 (int32 accumulators)", name, (long long)K);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!Ap || !Bp || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (ldc < N)
+        return fail(LB_EINVAL, "%s: ldc=%lld < N=%lld", name, (long long)ldc, (long long)N);
+    if (ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
+    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, 4))
+        return fail(LB_EINVAL, "%s: operands must be 16-byte aligned, C 4-byte aligned", name);
+    const int64_t KW = (K + 63) / 64;
+    if (KW > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: K too large", name);
+
+    int count = 0;
+    const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
+    lowbit::GemmArgs a;
+    bool transposed;
+    if (kind == lowbit::KIND_TBN) {
+        // the binary operand rides in scalar registers (one scalar source per instruction), the ternary one in
+        // vector registers: lanes own rows of C
+        a.Sp = reinterpret_cast<const uint32_t *>(Bp);
+        a.rowsS = (int)N;
+        a.Vp = reinterpret_cast<const uint32_t *>(Ap);
+        a.rowsV = (int)M;
+        transposed = true;
+    } else {
+        // lanes own columns of C (coalesced stores) unless N is too narrow to fill a wavefront and M is not
+        transposed = (N < 64 && M > N);
+        if (transposed) {
+            a.Sp = reinterpret_cast<const uint32_t *>(Bp);
+            a.rowsS = (int)N;
+            a.Vp = reinterpret_cast<const uint32_t *>(Ap);
+            a.rowsV = (int)M;
+        } else {
+            a.Sp = reinterpret_cast<const uint32_t *>(Ap);
+            a.rowsS = (int)M;
+            a.Vp = reinterpret_cast<const uint32_t *>(Bp);
+            a.rowsV = (int)N;
+        }
+    }
+    a.KW = (int)KW;
+    a.K = (int)K;
+    a.C = C;
+    a.ldc = ldc;
+    a.stream = static_cast<hipStream_t>(stream);
+    int v = g_forced[kind];
+    if (v < 0 || v >= count)
+        v = choose_variant(tab, count, a.rowsS, a.rowsV);
+    const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *lb_last_error(void) { return g_err; }
+
+int lb_format_version(void) { return LB_FORMAT_VERSION; }
+
+size_t packed_binary_bytes(int64_t rows, int64_t K) { return packed_bytes(rows, K, 8); }
+
+size_t packed_ternary_bytes(int64_t rows, int64_t K) { return packed_bytes(rows, K, 16); }
+
+int pack_binary(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint64_t *dst,
+                void *stream)
+{
+    return do_pack(false, "pack_binary", src, rows, K, stride_r, stride_k, dst, stream);
+}
+
+int pack_ternary(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint64_t *dst,
+                 void *stream)
+{
+    return do_pack(true, "pack_ternary", src, rows, K, stride_r, stride_k, dst, stream);
+}
+
+int gemm_bnn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream)
+{
+    return do_gemm(lowbit::KIND_BNN, "gemm_bnn", M, N, K, Ap, Bp, C, ldc, stream);
+}
+
+int gemm_tnn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream)
+{
+    return do_gemm(lowbit::KIND_TNN, "gemm_tnn", M, N, K, Ap, Bp, C, ldc, stream);
+}
+
+int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int32_t *C, int64_t ldc,
+             void *stream)
+{
+    return do_gemm(lowbit::KIND_TBN, "gemm_tbn", M, N, K, Ap, Bp, C, ldc, stream);
+}
+
+int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                 int32_t *C, int64_t ldc, void *stream)
+{
+    const char *name = "gemm_i8_mfma";
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    // |a*b| <= 2^14, so the int32 sum is safe up to K = 2^17 - 1 for arbitrary int8 inputs
+    if (K > 131071)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 131071 (int32 accumulation of int8 products)", name,
+                    (long long)K);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!A || !B || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (lda < K || ldb < N || ldc < N)
+        return fail(LB_EINVAL, "%s: lda=%lld ldb=%lld ldc=%lld too small", name, (long long)lda, (long long)ldb,
+                    (long long)ldc);
+    if (lda > INT64_MAX / M || ldb > INT64_MAX / K || ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
+    if (!aligned(C, 4))
+        return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    const hipError_t e = lowbit::launch_gemm_i8(M, N, K, A, lda, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+int lb_set_variant(int op, int variant)
+{
+    int count = 0;
+    if (op < 0 || op > 2 || !lowbit::gemm_variants(op, &count))
+        return fail(LB_EINVAL, "lb_set_variant: op=%d out of range", op);
+    if (variant < -1 || variant >= count)
+        return fail(LB_EINVAL, "lb_set_variant: variant=%d out of range [-1,%d)", variant, count);
+    g_forced[op] = variant;
+    return LB_OK;
+}
+
+int lb_num_variants(int op)
+{
+    int count = 0;
+    if (op < 0 || op > 2)
+        return 0;
+    lowbit::gemm_variants(op, &count);
+    return count;
+}
+
+const char *lb_variant_name(int op, int variant)
+{
+    int count = 0;
+    if (op < 0 || op > 2)
+        return nullptr;
+    const lowbit::GemmVariant *tab = lowbit::gemm_variants(op, &count);
+    if (variant < 0 || variant >= count)
+        return nullptr;
+    return tab[variant].name;
+}
+
+}  // extern "C"

@@ -1,0 +1,312 @@
+// Tiled popcount GEMM kernels for gfx950 (binary / ternary / ternary-binary, Section III of the paper).
+//
+// Design (differs from the paper's NEON microkernels on purpose; see the notes at the end of this comment):
+//   * One operand ("S", the scalar side) is read with scalar loads straight into SGPRs: every lane of a
+//     wavefront works on the same TS bit strings of S, so they cost no vector registers and no LDS traffic.
+//   * The other operand ("V", the vector side) is staged through LDS once per workgroup and every lane owns
+//     TV bit strings of it (lane, lane+64, ...).  A wave therefore computes a TS x (64*TV) block of products
+//     and a workgroup of WAVES waves a (WAVES*TS) x (64*TV) block.
+//   * Per 32 depth positions and output the VALU executes
+//        BNN: x = s ^ v;                    acc += popcount(x)                     (2 instructions, eq. (6))
+//        TNN: m = nz_s & nz_v; u = (neg_s ^ neg_v) & m;  M += popcount(m); U += popcount(u)     (4 instructions)
+//        TBN: u = (neg_v ^ y_s) & nz_v;     U += popcount(u)   (+ a per-string popcount(nz_v))  (2 instructions)
+//     where nz = x+ | x- and neg = x-.  With P = popcount(z+), Q = popcount(z-) of eq. (7): M = P + Q and U = Q,
+//     so C = M - 2U (TNN) and C = popcount(nz_v) - 2U (TBN) are the integers eq. (7) defines; the forms need
+//     fewer instructions than evaluating z+ and z- separately because gfx950 has a three-input bit operation.
+//   * Accumulators are 32-bit; the epilogue applies eq. (6) / (7) and writes int32 C.
+//
+// The ternary planes are converted from the stored (x+, x-) pair to (nz, neg) while the tile is staged, so the
+// packed format in memory stays the paper's encoding.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lowbit_internal.h"
+
+namespace lowbit {
+
+namespace {
+
+constexpr int kPadEntries = 4;  // LDS row padding, in entries
+
+template <int KIND> struct Traits;
+template <> struct Traits<KIND_BNN> { static constexpr int SD = 2, VD = 2, ACC = 1; };
+template <> struct Traits<KIND_TNN> { static constexpr int SD = 4, VD = 4, ACC = 2; };
+template <> struct Traits<KIND_TBN> { static constexpr int SD = 2, VD = 4, ACC = 1; };  // S binary, V ternary
+
+template <int D> struct Vec;
+template <> struct Vec<2> { using type = uint2; };
+template <> struct Vec<4> { using type = uint4; };
+
+__device__ __forceinline__ uint2 zero_of(uint2) { return make_uint2(0u, 0u); }
+__device__ __forceinline__ uint4 zero_of(uint4) { return make_uint4(0u, 0u, 0u, 0u); }
+
+// stored (plus, minus) -> (nz, neg)
+__device__ __forceinline__ uint4 to_nz_neg(uint4 e) { return make_uint4(e.x | e.z, e.y | e.w, e.z, e.w); }
+__device__ __forceinline__ uint2 to_nz_neg(uint2 e) { return e; }
+
+// The compiler re-associates the bit logic and splits popcount-accumulate into two instructions when it sees
+// plain C, so the three hot instructions are pinned with inline assembly.  `s` operands live in SGPRs (one
+// scalar source per VALU instruction is the limit of this ISA generation).
+__device__ __forceinline__ uint32_t and_sv(uint32_t s, uint32_t v)
+{
+    uint32_t r;
+    asm("v_and_b32 %0, %1, %2" : "=v"(r) : "s"(s), "v"(v));
+    return r;
+}
+__device__ __forceinline__ uint32_t xor_sv(uint32_t s, uint32_t v)
+{
+    uint32_t r;
+    asm("v_xor_b32 %0, %1, %2" : "=v"(r) : "s"(s), "v"(v));
+    return r;
+}
+// (s ^ v) & m : three-input bit operation, truth table built from a=0xF0, b=0xCC, c=0xAA -> (a^b)&c = 0x28
+__device__ __forceinline__ uint32_t xor_and_svv(uint32_t s, uint32_t v, uint32_t m)
+{
+    uint32_t r;
+    asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x28" : "=v"(r) : "s"(s), "v"(v), "v"(m));
+    return r;
+}
+// acc += popcount(x) in one instruction
+__device__ __forceinline__ void popc_acc(int32_t &acc, uint32_t x)
+{
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
+}
+
+template <int KIND, int TS, int TV, int WAVES, int KG, bool TR>
+__global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
+                                                               const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
+                                                               int KW, int K, int32_t *__restrict__ C, int64_t ldc,
+                                                               int nSB, int nVB, int tiles_per_xcd)
+{
+    using T = Traits<KIND>;
+    constexpr int SD = T::SD, VD = T::VD;
+    using SVec = typename Vec<SD>::type;
+    using VVec = typename Vec<VD>::type;
+    constexpr int NV = 64 * TV;
+    constexpr int STRIDE = NV + kPadEntries;
+    constexpr int UNITS = TV * KG;            // wave-wide loads per stage
+    static_assert(UNITS % WAVES == 0, "stage units must divide among the waves");
+    constexpr int UPW = UNITS / WAVES;        // per wave
+
+    __shared__ VVec lds[2][KG * STRIDE];
+
+    // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give each XCD a contiguous
+    // range of tiles; within it the S blocks of one V tile are adjacent and share that XCD's L2.
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nSB * nVB)
+        return;
+    const int vb = idx / nSB, sb = idx - vb * nSB;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int s0 = (sb * WAVES + wave) * TS;
+    const int v0 = vb * NV;
+
+    const SVec *__restrict__ Sv = reinterpret_cast<const SVec *>(Sp);
+    const VVec *__restrict__ Vv = reinterpret_cast<const VVec *>(Vp);
+
+    // row pointers of this wave's S strings (clamped: out-of-range rows recompute the last row, never stored)
+    const SVec *srow[TS];
+#pragma unroll
+    for (int i = 0; i < TS; ++i) {
+        int r = s0 + i;
+        r = r < rowsS ? r : rowsS - 1;
+        srow[i] = Sv + (int64_t)r * KW;
+    }
+
+    int32_t acc[T::ACC][TS][TV];
+#pragma unroll
+    for (int a = 0; a < T::ACC; ++a)
+#pragma unroll
+        for (int i = 0; i < TS; ++i)
+#pragma unroll
+            for (int t = 0; t < TV; ++t)
+                acc[a][i][t] = 0;
+    int32_t nnz[TV];
+#pragma unroll
+    for (int t = 0; t < TV; ++t)
+        nnz[t] = 0;
+
+    // stage bookkeeping: unit u = wave*UPW + j covers V strings vseg*64 + lane at depth word g
+    VVec pre[UPW];
+    auto fetch = [&](int kg0) {
+#pragma unroll
+        for (int j = 0; j < UPW; ++j) {
+            const int u = wave * UPW + j;
+            const int vseg = u / KG, g = u % KG;
+            const int v = v0 + vseg * 64 + lane;
+            const int kg = kg0 + g;
+            VVec e = zero_of(VVec{});
+            if (v < rowsV && kg < KW)
+                e = Vv[(int64_t)v * KW + kg];
+            pre[j] = e;
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < UPW; ++j) {
+            const int u = wave * UPW + j;
+            const int vseg = u / KG, g = u % KG;
+            lds[buf][g * STRIDE + vseg * 64 + lane] = to_nz_neg(pre[j]);
+        }
+    };
+
+    const int nchunks = (KW + KG - 1) / KG;
+    fetch(0);
+    commit(0);
+    __syncthreads();
+
+    for (int c = 0; c < nchunks; ++c) {
+        const int buf = c & 1;
+        const int kg0 = c * KG;
+        if (c + 1 < nchunks)
+            fetch(kg0 + KG);
+        const int gmax = (KW - kg0) < KG ? (KW - kg0) : KG;
+        for (int g = 0; g < gmax; ++g) {
+            SVec sv[TS];
+#pragma unroll
+            for (int i = 0; i < TS; ++i)
+                sv[i] = srow[i][kg0 + g];
+            uint32_t snz0[TS], snz1[TS];
+            if constexpr (KIND == KIND_TNN) {
+#pragma unroll
+                for (int i = 0; i < TS; ++i) {
+                    snz0[i] = sv[i].x | sv[i].z;
+                    snz1[i] = sv[i].y | sv[i].w;
+                }
+            }
+            VVec bnext = lds[buf][g * STRIDE + lane];
+#pragma unroll
+            for (int t = 0; t < TV; ++t) {
+                const VVec b = bnext;
+                if (t + 1 < TV)
+                    bnext = lds[buf][g * STRIDE + (t + 1) * 64 + lane];
+                if constexpr (KIND == KIND_BNN) {
+#pragma unroll
+                    for (int i = 0; i < TS; ++i) {
+                        popc_acc(acc[0][i][t], xor_sv(sv[i].x, b.x));
+                        popc_acc(acc[0][i][t], xor_sv(sv[i].y, b.y));
+                    }
+                } else if constexpr (KIND == KIND_TNN) {
+#pragma unroll
+                    for (int i = 0; i < TS; ++i) {
+                        const uint32_t m0 = and_sv(snz0[i], b.x), m1 = and_sv(snz1[i], b.y);
+                        const uint32_t u0 = xor_and_svv(sv[i].z, b.z, m0), u1 = xor_and_svv(sv[i].w, b.w, m1);
+                        popc_acc(acc[0][i][t], m0);
+                        popc_acc(acc[1][i][t], u0);
+                        popc_acc(acc[0][i][t], m1);
+                        popc_acc(acc[1][i][t], u1);
+                    }
+                } else {
+                    popc_acc(nnz[t], b.x);
+                    popc_acc(nnz[t], b.y);
+#pragma unroll
+                    for (int i = 0; i < TS; ++i) {
+                        popc_acc(acc[0][i][t], xor_and_svv(sv[i].x, b.z, b.x));
+                        popc_acc(acc[0][i][t], xor_and_svv(sv[i].y, b.w, b.y));
+                    }
+                }
+            }
+        }
+        if (c + 1 < nchunks)
+            commit(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: eq. (6) / (7), int32 store
+#pragma unroll
+    for (int t = 0; t < TV; ++t) {
+        const int v = v0 + t * 64 + lane;
+        int32_t out[TS];
+#pragma unroll
+        for (int i = 0; i < TS; ++i) {
+            if constexpr (KIND == KIND_BNN)
+                out[i] = K - 2 * acc[0][i][t];
+            else if constexpr (KIND == KIND_TNN)
+                out[i] = acc[0][i][t] - 2 * acc[1][i][t];
+            else
+                out[i] = nnz[t] - 2 * acc[0][i][t];
+        }
+        if (v < rowsV) {
+            if constexpr (!TR) {
+#pragma unroll
+                for (int i = 0; i < TS; ++i)
+                    if (s0 + i < rowsS)
+                        C[(int64_t)(s0 + i) * ldc + v] = out[i];
+            } else {
+                int32_t *crow = C + (int64_t)v * ldc + s0;
+                if constexpr (TS % 4 == 0) {
+                    if (s0 + TS <= rowsS && ((reinterpret_cast<uintptr_t>(crow) & 15) == 0)) {
+#pragma unroll
+                        for (int i = 0; i < TS; i += 4)
+                            *reinterpret_cast<int4 *>(crow + i) = make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);
+                        continue;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < TS; ++i)
+                    if (s0 + i < rowsS)
+                        crow[i] = out[i];
+            }
+        }
+    }
+}
+
+template <int KIND, int TS, int TV, int WAVES, int KG, bool TR>
+hipError_t launch(const GemmArgs &a)
+{
+    const int nSB = (a.rowsS + WAVES * TS - 1) / (WAVES * TS);
+    const int nVB = (a.rowsV + 64 * TV - 1) / (64 * TV);
+    const int64_t tiles = (int64_t)nSB * nVB;
+    const int tiles_per_xcd = (int)((tiles + 7) / 8);
+    const int64_t grid = (int64_t)tiles_per_xcd * 8;
+    if (grid > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
+                       a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd);
+    return hipGetLastError();
+}
+
+#define LB_VARIANT(KIND, TS, TV, WAVES, KG)                                                         \
+    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG, TS * WAVES, 64 * TV,                           \
+     &launch<KIND, TS, TV, WAVES, KG, false>, &launch<KIND, TS, TV, WAVES, KG, true>}
+
+const GemmVariant kBnn[] = {
+    LB_VARIANT(KIND_BNN, 8, 1, 4, 8),
+    LB_VARIANT(KIND_BNN, 8, 2, 4, 8),
+    LB_VARIANT(KIND_BNN, 8, 4, 4, 8),
+    LB_VARIANT(KIND_BNN, 8, 8, 4, 4),
+    LB_VARIANT(KIND_BNN, 16, 4, 4, 8),
+    LB_VARIANT(KIND_BNN, 16, 8, 4, 4),
+};
+const GemmVariant kTnn[] = {
+    LB_VARIANT(KIND_TNN, 8, 1, 4, 8),
+    LB_VARIANT(KIND_TNN, 8, 2, 4, 8),
+    LB_VARIANT(KIND_TNN, 8, 4, 4, 4),
+    LB_VARIANT(KIND_TNN, 8, 4, 8, 4),
+    LB_VARIANT(KIND_TNN, 8, 8, 4, 4),
+    LB_VARIANT(KIND_TNN, 8, 8, 8, 4),
+    LB_VARIANT(KIND_TNN, 4, 8, 8, 4),
+};
+const GemmVariant kTbn[] = {
+    LB_VARIANT(KIND_TBN, 8, 1, 4, 8),
+    LB_VARIANT(KIND_TBN, 8, 2, 4, 8),
+    LB_VARIANT(KIND_TBN, 8, 4, 4, 4),
+    LB_VARIANT(KIND_TBN, 16, 4, 4, 4),
+    LB_VARIANT(KIND_TBN, 16, 8, 4, 4),
+    LB_VARIANT(KIND_TBN, 16, 8, 8, 4),
+};
+
+}  // namespace
+
+const GemmVariant *gemm_variants(int kind, int *count)
+{
+    switch (kind) {
+    case KIND_BNN: *count = (int)(sizeof(kBnn) / sizeof(kBnn[0])); return kBnn;
+    case KIND_TNN: *count = (int)(sizeof(kTnn) / sizeof(kTnn[0])); return kTnn;
+    case KIND_TBN: *count = (int)(sizeof(kTbn) / sizeof(kTbn[0])); return kTbn;
+    default: *count = 0; return nullptr;
+    }
+}
+
+}  // namespace lowbit

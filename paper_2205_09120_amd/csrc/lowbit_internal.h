@@ -1,0 +1,40 @@
+// Internal declarations shared by the HIP translation units of the library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lowbit {
+
+enum Kind { KIND_BNN = 0, KIND_TNN = 1, KIND_TBN = 2 };
+
+// One tiled popcount GEMM launch.  S is the scalar-side packed operand (rowsS bit strings), V the vector-side
+// one (rowsV bit strings); product (s, v) is written to C[s*ldc + v], or to C[v*ldc + s] by the transposed
+// launcher.  Operand classes per kind: BNN S,V binary; TNN S,V ternary; TBN S binary, V ternary.
+struct GemmArgs {
+    const uint32_t *Sp;
+    const uint32_t *Vp;
+    int rowsS, rowsV, KW, K;
+    int32_t *C;
+    int64_t ldc;
+    hipStream_t stream;
+};
+
+struct GemmVariant {
+    const char *name;
+    int tileS, tileV;  // workgroup tile extents along S and V
+    hipError_t (*launch)(const GemmArgs &);
+    hipError_t (*launch_transposed)(const GemmArgs &);
+};
+
+const GemmVariant *gemm_variants(int kind, int *count);
+
+// Packing launchers (pack.hip).  Element (r,k) = src[r*stride_r + k*stride_k].
+hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
+                       uint64_t *dst, hipStream_t stream);
+
+// int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
+hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                          int32_t *C, int64_t ldc, hipStream_t stream);
+
+}  // namespace lowbit

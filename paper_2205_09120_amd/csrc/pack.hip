@@ -1,0 +1,246 @@
+// Packing kernels: int8 {-1,0,+1} / {-1,+1} matrices -> depth-contiguous 64-bit bit-plane words
+// (encodings of Section III-A of the paper; the role of PackNRowsA / PackNColsB in its Algorithms 1 and 2).
+//
+// Output format: see include/lowbit_gemm.h.  All kernels are HBM-bound streaming kernels: 1 byte read per
+// element, 1 or 2 bits written.
+//   * depth-contiguous source (stride_k == 1, e.g. A row-major): four lanes share one 64-bit word; each lane
+//     reads 16 consecutive bytes (one 128-bit load, fully coalesced), extracts 16 plus and 16 minus bits, and the
+//     quad exchanges its pieces with DPP moves so that every lane stores one 32-bit piece of the output.
+//   * depth-strided source (stride_r == 1, e.g. B row-major, packed along its columns): a lane reads one dword
+//     = 4 adjacent bit strings at one depth position (coalesced along the strings), shifts the sign / non-zero
+//     bit of each byte into four per-byte shift registers (8 depth positions per byte), transposes the bytes in
+//     registers, and the workgroup writes its 128 strings x 8 words tile through LDS so that stores are
+//     contiguous along the depth words.
+//   * anything else (odd strides, misaligned pointers): one thread per output word, byte loads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lowbit_internal.h"
+
+namespace lowbit {
+namespace {
+
+constexpr uint32_t kHi = 0x80808080u, kLo = 0x7f7f7f7fu;
+
+// bit 7 of each byte: byte is negative / byte is positive
+__device__ __forceinline__ uint32_t neg7(uint32_t x) { return x & kHi; }
+__device__ __forceinline__ uint32_t pos7(uint32_t x) { return ((x & kLo) + kLo) & ~x & kHi; }
+
+// gather bits 7,15,23,31 into bits 0..3
+__device__ __forceinline__ uint32_t gather4(uint32_t m)
+{
+    const uint32_t y = (m >> 7) | (m >> 14);
+    return (y | (y >> 14)) & 0xfu;
+}
+
+__device__ __forceinline__ uint32_t bits16(const uint4 &v, bool plus)
+{
+    uint32_t a = plus ? pos7(v.x) : neg7(v.x);
+    uint32_t b = plus ? pos7(v.y) : neg7(v.y);
+    uint32_t c = plus ? pos7(v.z) : neg7(v.z);
+    uint32_t d = plus ? pos7(v.w) : neg7(v.w);
+    return gather4(a) | (gather4(b) << 4) | (gather4(c) << 8) | (gather4(d) << 12);
+}
+
+// value of `x` held by lane (quad base + Q) of every quad
+template <int Q> __device__ __forceinline__ uint32_t quad_bcast(uint32_t x)
+{
+    constexpr int ctrl = Q | (Q << 2) | (Q << 4) | (Q << 6);  // quad_perm:[Q,Q,Q,Q]
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, ctrl, 0xf, 0xf, true);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// depth-contiguous source.  Thread t handles bytes [16*(t%4), +16) of word (t/4) in row-major (r, w) order.
+// Requires stride_r % 16 == 0 and a 16-byte aligned src.
+template <bool TERNARY>
+__global__ __launch_bounds__(256) void pack_kcontig_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                           int64_t KW, int64_t stride_r, uint32_t *__restrict__ dst)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t word = t >> 2;  // r*KW + w
+    const int q = (int)(t & 3);
+    const bool live = word < rows * KW;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (live) {
+        const int64_t r = word / KW, w = word - r * KW;
+        const int64_t k0 = w * 64 + q * 16;
+        const int8_t *p = src + r * stride_r + k0;
+        if (k0 + 16 <= K) {
+            v = *reinterpret_cast<const uint4 *>(p);
+        } else if (k0 < K) {
+            uint32_t tmp[4] = {0u, 0u, 0u, 0u};
+            for (int i = 0; i < (int)(K - k0); ++i)
+                tmp[i >> 2] |= (uint32_t)(uint8_t)p[i] << (8 * (i & 3));
+            v = make_uint4(tmp[0], tmp[1], tmp[2], tmp[3]);
+        }
+    }
+    const uint32_t mine = bits16(v, false) | (TERNARY ? (bits16(v, true) << 16) : 0u);  // minus low, plus high
+    const uint32_t p0 = quad_bcast<0>(mine), p1 = quad_bcast<1>(mine), p2 = quad_bcast<2>(mine),
+                   p3 = quad_bcast<3>(mine);
+    if (!live)
+        return;
+    if (TERNARY) {
+        // dwords of the 16-byte entry: plus_lo, plus_hi, minus_lo, minus_hi
+        uint32_t out;
+        if (q == 0)
+            out = (p0 >> 16) | (p1 & 0xffff0000u);
+        else if (q == 1)
+            out = (p2 >> 16) | (p3 & 0xffff0000u);
+        else if (q == 2)
+            out = (p0 & 0xffffu) | (p1 << 16);
+        else
+            out = (p2 & 0xffffu) | (p3 << 16);
+        dst[word * 4 + q] = out;
+    } else {
+        if (q == 0)
+            dst[word * 2] = (p0 & 0xffffu) | (p1 << 16);
+        else if (q == 1)
+            dst[word * 2 + 1] = (p2 & 0xffffu) | (p3 << 16);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// depth-strided source.  Workgroup tile: 128 bit strings x 8 depth words.  Thread (quad = tid%32, w = tid/32).
+// Requires stride_k % 4 == 0 and a 4-byte aligned src.
+template <bool TERNARY>
+__global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                            int64_t KW, int64_t stride_k, uint32_t *__restrict__ dst,
+                                                            int64_t nRB)
+{
+    constexpr int ED = TERNARY ? 4 : 2;       // dwords per output entry
+    __shared__ uint32_t tile[128][8 * ED + 1];
+
+    const int64_t rb = blockIdx.x % nRB, wb = blockIdx.x / nRB;
+    const int quad = threadIdx.x & 31, wl = threadIdx.x >> 5;
+    const int64_t r0 = rb * 128 + quad * 4;
+    const int64_t w = wb * 8 + wl;
+    const int64_t kbase = w * 64;
+
+    uint32_t neg[8], pos[8];
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb) {
+        uint32_t an = 0u, ap = 0u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t k = kbase + kb * 8 + j;
+            uint32_t x = 0u;
+            if (k < K && r0 < rows) {
+                const int8_t *p = src + k * stride_k + r0;
+                if (r0 + 4 <= rows) {
+                    x = *reinterpret_cast<const uint32_t *>(p);
+                } else {
+                    for (int i = 0; i < (int)(rows - r0); ++i)
+                        x |= (uint32_t)(uint8_t)p[i] << (8 * i);
+                }
+            }
+            an = (an >> 1) | neg7(x);
+            if (TERNARY)
+                ap = (ap >> 1) | pos7(x);
+        }
+        neg[kb] = an;  // byte i = 8 depth bits of string r0+i
+        pos[kb] = ap;
+    }
+    // byte transpose: string i gets bytes i of neg[0..3] (low dword) and neg[4..7] (high dword)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        auto col = [&](const uint32_t *a, int base) {
+            return ((a[base] >> (8 * i)) & 0xffu) | (((a[base + 1] >> (8 * i)) & 0xffu) << 8) |
+                   (((a[base + 2] >> (8 * i)) & 0xffu) << 16) | (((a[base + 3] >> (8 * i)) & 0xffu) << 24);
+        };
+        uint32_t *e = &tile[quad * 4 + i][wl * ED];
+        if (TERNARY) {
+            e[0] = col(pos, 0);
+            e[1] = col(pos, 4);
+            e[2] = col(neg, 0);
+            e[3] = col(neg, 4);
+        } else {
+            e[0] = col(neg, 0);
+            e[1] = col(neg, 4);
+        }
+    }
+    __syncthreads();
+    // write out: 8*ED dwords per string are contiguous in dst
+    constexpr int DW = 8 * ED;
+    for (int idx = threadIdx.x; idx < 128 * DW; idx += 256) {
+        const int rl = idx / DW, d = idx % DW;
+        const int64_t r = rb * 128 + rl;
+        const int64_t ww = wb * 8 + d / ED;
+        if (r < rows && ww < KW)
+            dst[(r * KW + ww) * ED + d % ED] = tile[rl][d];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// any strides: one thread per output word
+template <bool TERNARY>
+__global__ __launch_bounds__(256) void pack_generic_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                           int64_t KW, int64_t stride_r, int64_t stride_k,
+                                                           uint64_t *__restrict__ dst)
+{
+    const int64_t word = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (word >= rows * KW)
+        return;
+    const int64_t r = word / KW, w = word - r * KW;
+    uint64_t plus = 0, minus = 0;
+    const int64_t k0 = w * 64;
+    const int n = (int)((K - k0) < 64 ? (K - k0) : 64);
+    for (int b = 0; b < n; ++b) {
+        const int8_t x = src[r * stride_r + (k0 + b) * stride_k];
+        plus |= (uint64_t)(x > 0) << b;
+        minus |= (uint64_t)(x < 0) << b;
+    }
+    if (TERNARY) {
+        dst[word * 2] = plus;
+        dst[word * 2 + 1] = minus;
+    } else {
+        dst[word] = minus;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
+                       uint64_t *dst, hipStream_t stream)
+{
+    const int64_t KW = (K + 63) / 64;
+    const int64_t words = rows * KW;
+    if (words == 0)
+        return hipSuccess;
+    const uintptr_t sa = reinterpret_cast<uintptr_t>(src);
+    uint32_t *d32 = reinterpret_cast<uint32_t *>(dst);
+    if (stride_k == 1 && (stride_r % 16) == 0 && (sa % 16) == 0) {
+        const int64_t blocks = (words * 4 + 255) / 256;
+        if (blocks > 0x7fffffffLL)
+            return hipErrorInvalidConfiguration;
+        if (ternary)
+            hipLaunchKernelGGL(pack_kcontig_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_r, d32);
+        else
+            hipLaunchKernelGGL(pack_kcontig_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_r, d32);
+    } else if (stride_r == 1 && (stride_k % 4) == 0 && (sa % 4) == 0) {
+        const int64_t nRB = (rows + 127) / 128, nWB = (KW + 7) / 8;
+        const int64_t blocks = nRB * nWB;
+        if (blocks > 0x7fffffffLL)
+            return hipErrorInvalidConfiguration;
+        if (ternary)
+            hipLaunchKernelGGL(pack_kstrided_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_k, d32, nRB);
+        else
+            hipLaunchKernelGGL(pack_kstrided_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_k, d32, nRB);
+    } else {
+        const int64_t blocks = (words + 255) / 256;
+        if (blocks > 0x7fffffffLL)
+            return hipErrorInvalidConfiguration;
+        if (ternary)
+            hipLaunchKernelGGL(pack_generic_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_r, stride_k, dst);
+        else
+            hipLaunchKernelGGL(pack_generic_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
+                               KW, stride_r, stride_k, dst);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lowbit

@@ -1,0 +1,219 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element (bit-exact).
+
+Every test prints what it is about to run (shape, seed, entry point) and flushes, so a failing run names its case.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import bitref, oracle
+from paper_2205_09120_amd import binding as lb
+from paper_2205_09120_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lb.lib()  # fail loudly if the HIP library is missing
+    yield
+    for op in ("bnn", "tnn", "tbn"):
+        lb.lb_set_variant(op, -1)
+
+
+def dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(x).cuda()
+
+
+def words(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def run_gemm(kind, A, B, C=None, ldc=None):
+    M, K = A.shape
+    N = B.shape[1]
+    dA, dB = dev(A), dev(B)
+    Ap, Bp = lb.pack_a(kind, dA), lb.pack_b(kind, dB)
+    out = lb.gemm(kind, M, N, K, Ap, Bp, C, ldc)
+    torch.cuda.synchronize()
+    return out
+
+
+# ------------------------------------------------------------------------------------------------ packing
+
+PACK_SHAPES = [(1, 1), (3, 63), (5, 64), (7, 65), (64, 576), (130, 1000), (257, 129), (33, 4096 + 17)]
+
+
+@pytest.mark.parametrize("rows,K", PACK_SHAPES)
+@pytest.mark.parametrize("ternary", [True, False])
+def test_pack_depth_contiguous(rows, K, ternary):
+    say(f"pack depth-contiguous rows={rows} K={K} ternary={ternary}")
+    X, _ = synth.make_custom("tnn" if ternary else "bnn", rows, 1, K, seed=rows * 7 + K)
+    for lda in (K, ((K + 15) // 16) * 16, ((K + 15) // 16) * 16 + 16):
+        buf = np.zeros((rows, lda), dtype=np.int8)
+        buf[:, :K] = X
+        d = dev(buf)
+        f = lb.pack_ternary if ternary else lb.pack_binary
+        got = words(f(d, rows, K, lda, 1))
+        torch.cuda.synchronize()
+        want = (bitref.pack_ternary(X) if ternary else bitref.pack_binary(X)).reshape(-1)
+        assert np.array_equal(got, want), f"lda={lda}"
+
+
+@pytest.mark.parametrize("rows,K", PACK_SHAPES + [(784, 2304), (8, 300)])
+@pytest.mark.parametrize("ternary", [True, False])
+def test_pack_depth_strided(rows, K, ternary):
+    say(f"pack depth-strided rows={rows} K={K} ternary={ternary}")
+    _, B = synth.make_custom("tnn" if ternary else "bnn", 1, rows, K, seed=rows * 3 + K)   # K x rows
+    for ldb in (rows, ((rows + 3) // 4) * 4, ((rows + 3) // 4) * 4 + 8):
+        buf = np.zeros((K, ldb), dtype=np.int8)
+        buf[:, :rows] = B
+        d = dev(buf)
+        f = lb.pack_ternary if ternary else lb.pack_binary
+        got = words(f(d, rows, K, 1, ldb))
+        torch.cuda.synchronize()
+        Xt = np.ascontiguousarray(B.T)
+        want = (bitref.pack_ternary(Xt) if ternary else bitref.pack_binary(Xt)).reshape(-1)
+        assert np.array_equal(got, want), f"ldb={ldb}"
+
+
+def test_pack_misaligned_source_and_illegal_values():
+    say("pack misaligned source / values outside the legal sets")
+    rng = np.random.default_rng(5)
+    X = rng.integers(-128, 128, size=(9, 200), dtype=np.int8)         # any int8: encoded by sign
+    big = np.zeros(9 * 200 + 3, dtype=np.int8)
+    big[3:] = X.reshape(-1)
+    d = dev(big)[3:]                                                  # data pointer off by 3 bytes
+    got_t = words(lb.pack_ternary(d, 9, 200, 200, 1))
+    got_b = words(lb.pack_binary(d, 9, 200, 200, 1))
+    torch.cuda.synchronize()
+    assert np.array_equal(got_t, bitref.pack_ternary(X).reshape(-1))
+    assert np.array_equal(got_b, bitref.pack_binary(X).reshape(-1))
+    dX = dev(X)
+    assert np.array_equal(words(lb.pack_ternary(dX, 9, 200, 200, 1)), bitref.pack_ternary(X).reshape(-1))
+    Xt = np.ascontiguousarray(X.T)                                    # 200 x 9 viewed as depth-strided (rows=9... )
+    dXt = dev(Xt)
+    got = words(lb.pack_ternary(dXt, 9, 200, 1, 9))
+    torch.cuda.synchronize()
+    assert np.array_equal(got, bitref.pack_ternary(X).reshape(-1))
+    planes = got.reshape(-1, 2)
+    assert not np.any(planes[:, 0] & planes[:, 1])                    # never the invalid code (1,1)
+
+
+# ------------------------------------------------------------------------------------------------ GEMM, benchmark configs
+
+@pytest.mark.parametrize("name", ["cfg1_tnn_conv3x3x64_16x16", "cfg2_bnn_conv3x3x128_56x56",
+                                  "cfg3_tbn_conv3x3x256_28x28", "cfg5_tnn_fc_n8", "cfg5_tbn_fc_n8",
+                                  "cfg5_bnn_fc_n8"])
+def test_gemm_configs_full(name):
+    w = synth.WORKLOADS[name]
+    say(f"gemm_{w.kind} {name} M={w.M} N={w.N} K={w.K} seed={w.seed}")
+    A, B = synth.make_inputs(w)
+    got = run_gemm(w.kind, A, B).cpu().numpy()
+    want = oracle.gemm(A, B)
+    assert np.array_equal(got, want)
+
+
+def test_gemm_headline_full_size():
+    """cfg4 at full size in the default launch configuration (the one bench.py times): every element."""
+    w = synth.WORKLOADS[synth.HEADLINE]
+    say(f"gemm_tnn {w.name} M={w.M} N={w.N} K={w.K} seed={w.seed} (full oracle)")
+    A, B = synth.make_inputs(w)
+    got = run_gemm("tnn", A, B).cpu().numpy()
+    say("  gpu done; running oracle")
+    want = oracle.gemm(A, B)
+    assert np.array_equal(got, want)
+    n11_bound = ((A != 0).sum(axis=1, dtype=np.int64)[:, None])       # |c| <= nnz(row) is implied by |c| <= n11
+    assert np.all(np.abs(got) <= n11_bound)
+
+
+# ------------------------------------------------------------------------------------------------ GEMM, edge shapes, all variants
+
+EDGE_SHAPES = [(1, 1, 1), (1, 1, 64), (1, 70, 65), (70, 1, 63), (5, 7, 130), (33, 65, 64), (64, 64, 128),
+               (65, 129, 200), (100, 300, 577), (8, 520, 1000), (130, 8, 2000), (257, 513, 320)]
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_edge_shapes_all_variants(kind):
+    nvar = lb.lb_num_variants(kind)
+    try:
+        for v in list(range(nvar)) + [-1]:
+            lb.lb_set_variant(kind, v)
+            for (M, N, K) in EDGE_SHAPES:
+                say(f"gemm_{kind} variant={v} ({lb.lb_variant_name(kind, v)}) M={M} N={N} K={K}")
+                A, B = synth.make_custom(kind, M, N, K, seed=M + 3 * N + 7 * K)
+                got = run_gemm(kind, A, B).cpu().numpy()
+                assert np.array_equal(got, oracle.gemm(A, B)), (v, M, N, K)
+    finally:
+        lb.lb_set_variant(kind, -1)
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_ldc_and_untouched_padding(kind):
+    M, N, K, ldc = 37, 50, 333, 64
+    say(f"gemm_{kind} ldc M={M} N={N} K={K} ldc={ldc}")
+    A, B = synth.make_custom(kind, M, N, K, seed=99)
+    C = torch.full((M, ldc), -777, dtype=torch.int32, device="cuda")
+    run_gemm(kind, A, B, C=C, ldc=ldc)
+    got = C.cpu().numpy()
+    assert np.array_equal(got[:, :N], oracle.gemm(A, B))
+    assert np.all(got[:, N:] == -777)
+
+
+def test_same_no_zero_matrix_through_all_three_entry_points():
+    """A ternary matrix without zeros is also a binary matrix: the three entry points must agree on it."""
+    say("cross-check tnn/tbn/bnn on +-1 matrices")
+    A, B = synth.make_custom("bnn", 77, 91, 450, seed=12)
+    want = oracle.gemm(A, B)
+    for kind in ("bnn", "tnn", "tbn"):
+        assert np.array_equal(run_gemm(kind, A, B).cpu().numpy(), want), kind
+
+
+def test_special_cases_on_gpu():
+    say("special cases: zero matrix, all ones, negation")
+    A, B = synth.make_custom("tnn", 40, 70, 260, seed=21)
+    assert not run_gemm("tnn", np.zeros_like(A), B).cpu().numpy().any()
+    ones = np.ones_like(A)
+    assert np.array_equal(run_gemm("tnn", ones, B).cpu().numpy(),
+                          np.broadcast_to(B.sum(axis=0, dtype=np.int32), (40, 70)))
+    assert np.array_equal(run_gemm("tnn", -A, B).cpu().numpy(), -oracle.gemm(A, B))
+
+
+def test_deterministic():
+    w = synth.WORKLOADS["cfg3_tbn_conv3x3x256_28x28"]
+    say("determinism", w.name)
+    A, B = synth.make_inputs(w)
+    a = run_gemm(w.kind, A, B).cpu().numpy()
+    b = run_gemm(w.kind, A, B).cpu().numpy()
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------ int8 matrix-core comparator
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (128, 128, 64), (257, 300, 1000),
+                                   (512, 784, 2304), (33, 8, 4096)])
+def test_i8_mfma(M, N, K):
+    say(f"gemm_i8_mfma M={M} N={N} K={K}")
+    rng = np.random.default_rng(M + N + K)
+    A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+    got = lb.gemm_i8_mfma(M, N, K, dev(A), K, dev(B), N)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.gemm(A, B))
+
+
+def test_i8_mfma_on_ternary_config():
+    w = synth.WORKLOADS["cfg1_tnn_conv3x3x64_16x16"]
+    say("gemm_i8_mfma", w.name)
+    A, B = synth.make_inputs(w)
+    got = lb.gemm_i8_mfma(w.M, w.N, w.K, dev(A), w.K, dev(B), w.N)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.gemm(A, B))
