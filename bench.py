@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the low-bit GEMM hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input of the headline workload
+(cfg4: ternary x ternary, A 1024 x 4608, B 4608 x 50176 = batch 16 of 56x56 im2col):
+    pack_ternary(A)  ->  pack_ternary(B)  ->  gemm_tnn  ->  int32 C
+with the int8 inputs already resident in HBM.  value = 2*M*N*K / (step time), in TOPS.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline      the dominant kernel (gemm_tnn) against the 32-bit VALU peak of the chip
+  cpu_baseline  the CPU oracle (plain int32 triple loop) timed on a bounded row slice of the same workload
+  extra         gemm-only and pack-only times, the int8 matrix-core comparator, the other configurations
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# 32-bit VALU peak of MI355X: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
+# (= the 157.3 TFLOP/s fp32 vector figure divided by 2 for FMA and by 2 for packed issue).
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
+# lane-instructions per output and per 32 depth positions executed by the shipped kernels
+LANE_INSTR = {"tnn": 4, "tbn": 2, "bnn": 2}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM bytes) so that profiler byte counters "
+                         "collected over this command can be scaled")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2205_09120_amd import binding as lb
+    from paper_2205_09120_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    lb.lib()  # raises if the HIP library is missing
+
+    w = synth.WORKLOADS[synth.HEADLINE]
+    A, B = synth.make_inputs(w)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    M, N, K = w.M, w.N, w.K
+    Ap = torch.empty(lb.packed_ternary_bytes(M, K) // 8, dtype=torch.int64, device="cuda")
+    Bp = torch.empty(lb.packed_ternary_bytes(N, K) // 8, dtype=torch.int64, device="cuda")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+
+    def step(ev=None):
+        lb.pack_ternary(dA, M, K, K, 1, Ap)
+        lb.pack_ternary(dB, N, K, 1, N, Bp)
+        if ev is not None:
+            ev[0].record()
+        lb.gemm_tnn(M, N, K, Ap, Bp, C, N)
+        if ev is not None:
+            ev[1].record()
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)      # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(evs[i])
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    step_s = wall / args.steps
+    gemm_s = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+    dev_step_s = e0.elapsed_time(e1) * 1e-3 / args.steps
+
+    lane_ops = M * N * (K / 32.0) * LANE_INSTR["tnn"]
+    achieved = lane_ops / gemm_s / 1e12
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "gemm_tnn_cfg4_hbm_traffic.txt")
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+    out = {
+        "metric": "effective TOPS (2*M*N*K/s), TNN GEMM incl. packing of both operands",
+        "value": w.ops / step_s / 1e12,
+        "unit": "TOPS",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": step_s * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "kind": "tnn", "M": M, "N": N, "K": K, "seed": w.seed,
+                   "step": "pack_ternary(A) + pack_ternary(B) + gemm_tnn", "p_zero": w.p0_a},
+        "roofline": {"bound": "alu", "kernel": "gemm_tnn (gemm_popc_kernel)", "achieved": achieved,
+                     "peak": VALU_PEAK_TOPS, "unit": "TOP/s (32-bit VALU lane-instructions)",
+                     "frac": achieved / VALU_PEAK_TOPS, "traffic": traffic,
+                     "lane_instr_per_output_per_32_depth": LANE_INSTR["tnn"], "kernel_ms": gemm_s * 1e3},
+    }
+
+    extra = {"device_ms_per_step": dev_step_s * 1e3, "gemm_only_tops": w.ops / gemm_s / 1e12}
+
+    def dev_time(fn, iters, warm=3):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / iters
+
+    def graph_time(fn, per_graph, replays):
+        """Kernel time without host launch gaps: capture per_graph launches into one HIP graph and replay it."""
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(per_graph):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(replays):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / (replays * per_graph)
+
+    if not args.no_extra:
+        tpa = dev_time(lambda: lb.pack_ternary(dA, M, K, K, 1, Ap), 50)
+        tpb = dev_time(lambda: lb.pack_ternary(dB, N, K, 1, N, Bp), 50)
+        extra["pack_a_us"] = tpa * 1e6
+        extra["pack_b_us"] = tpb * 1e6
+        extra["pack_b_gbs"] = (B.nbytes + Bp.numel() * 8) / tpb / 1e9
+        ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
+        extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
+        extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
+        others = {}
+        del dB, Bp, C
+        for name, ww in synth.WORKLOADS.items():
+            if name == w.name:
+                continue
+            a_, b_ = synth.make_inputs(ww)
+            da, db = torch.from_numpy(a_).cuda(), torch.from_numpy(b_).cuda()
+            ap_, bp_ = lb.pack_a(ww.kind, da), lb.pack_b(ww.kind, db)
+            c_ = torch.empty((ww.M, ww.N), dtype=torch.int32, device="cuda")
+            t = graph_time(lambda: lb.gemm(ww.kind, ww.M, ww.N, ww.K, ap_, bp_, c_, ww.N), 20, 20)
+            t8 = graph_time(lambda: lb.gemm_i8_mfma(ww.M, ww.N, ww.K, da, ww.K, db, ww.N, c_, ww.N), 20, 20)
+            packed_bytes = (ap_.numel() + bp_.numel()) * 8 + c_.numel() * 4
+            others[name] = {"gemm_us": t * 1e6, "tops": ww.ops / t / 1e12, "int8_mfma_us": t8 * 1e6,
+                            "speedup_vs_int8_mfma": t8 / t,
+                            "valu_frac": ww.M * ww.N * (ww.K / 32.0) * LANE_INSTR[ww.kind] / t / 1e12 / VALU_PEAK_TOPS,
+                            "hbm_frac": packed_bytes / t / 1e9 / HBM_PEAK_GBS}
+        extra["other_configs_gemm_only_warm"] = others
+    out["extra"] = extra
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        rows = 32
+        t0 = time.perf_counter()
+        _, used = oracle.gemm_threads(np.ascontiguousarray(A[:rows]), B)
+        probe = time.perf_counter() - t0
+        rows = int(min(M, max(32, rows * 12.0 / max(probe, 1e-3))))
+        t0 = time.perf_counter()
+        _, used = oracle.gemm_threads(np.ascontiguousarray(A[:rows]), B)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * N * K / dt / 1e12, "unit": "TOPS", "cores": used,
+                               "kind": "oracle",
+                               "sample": f"first {rows} of {M} rows of A against the full B ({dt:.1f} s of CPU time)"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

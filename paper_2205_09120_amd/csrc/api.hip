@@ -74,18 +74,25 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
     return LB_OK;
 }
 
-// Pick a tile variant: the largest workgroup tile that still yields enough workgroups to occupy the device
-// several times over; smaller problems fall through to smaller tiles.
+// Pick a tile variant: the highest-ranked one that still yields enough workgroups to occupy the 256 compute
+// units several times over; problems too small for that take the variant with the most workgroups.
 int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV)
 {
-    constexpr int64_t kWanted = 256 * 6;  // workgroups: compute units x a few rounds
-    int best = 0;
+    constexpr int64_t kWanted = 256 * 6;
+    int best = -1, fallback = 0;
+    int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
+        if (tab[i].rank <= 0)
+            continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
-        if (wg >= kWanted)
-            best = i;  // tables are ordered by increasing tile size
+        if (wg >= kWanted && (best < 0 || tab[i].rank > tab[best].rank))
+            best = i;
+        if (wg > fallback_wg) {
+            fallback_wg = wg;
+            fallback = i;
+        }
     }
-    return best;
+    return best >= 0 ? best : fallback;
 }
 
 int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,

@@ -267,34 +267,47 @@ hipError_t launch(const GemmArgs &a)
     return hipGetLastError();
 }
 
-#define LB_VARIANT(KIND, TS, TV, WAVES, KG)                                                         \
-    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG, TS * WAVES, 64 * TV,                           \
+#define LB_VARIANT(RANK, KIND, TS, TV, WAVES, KG)                                                   \
+    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG, RANK, TS * WAVES, 64 * TV,                     \
      &launch<KIND, TS, TV, WAVES, KG, false>, &launch<KIND, TS, TV, WAVES, KG, true>}
 
+// rank: preference of the shape-based selection (higher wins among the variants that yield enough workgroups;
+// 0 = only reachable through lb_set_variant)
 const GemmVariant kBnn[] = {
-    LB_VARIANT(KIND_BNN, 8, 1, 4, 8),
-    LB_VARIANT(KIND_BNN, 8, 2, 4, 8),
-    LB_VARIANT(KIND_BNN, 8, 4, 4, 8),
-    LB_VARIANT(KIND_BNN, 8, 8, 4, 4),
-    LB_VARIANT(KIND_BNN, 16, 4, 4, 8),
-    LB_VARIANT(KIND_BNN, 16, 8, 4, 4),
+    LB_VARIANT(1, KIND_BNN, 8, 1, 4, 8),
+    LB_VARIANT(2, KIND_BNN, 8, 2, 4, 8),
+    LB_VARIANT(3, KIND_BNN, 8, 4, 4, 8),
+    LB_VARIANT(0, KIND_BNN, 8, 8, 4, 4),
+    LB_VARIANT(0, KIND_BNN, 16, 4, 4, 8),
+    LB_VARIANT(0, KIND_BNN, 16, 8, 4, 4),
+    LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8),
+    LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8),
+    LB_VARIANT(0, KIND_BNN, 8, 4, 2, 8),
 };
 const GemmVariant kTnn[] = {
-    LB_VARIANT(KIND_TNN, 8, 1, 4, 8),
-    LB_VARIANT(KIND_TNN, 8, 2, 4, 8),
-    LB_VARIANT(KIND_TNN, 8, 4, 4, 4),
-    LB_VARIANT(KIND_TNN, 8, 4, 8, 4),
-    LB_VARIANT(KIND_TNN, 8, 8, 4, 4),
-    LB_VARIANT(KIND_TNN, 8, 8, 8, 4),
-    LB_VARIANT(KIND_TNN, 4, 8, 8, 4),
+    LB_VARIANT(1, KIND_TNN, 8, 1, 4, 8),
+    LB_VARIANT(2, KIND_TNN, 8, 2, 4, 8),
+    LB_VARIANT(3, KIND_TNN, 8, 4, 4, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 8, 4, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 8, 8, 4),
+    LB_VARIANT(0, KIND_TNN, 4, 8, 8, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 4, 8),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 2, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 6, 4, 4),
+    LB_VARIANT(0, KIND_TNN, 12, 4, 4, 4),
+    LB_VARIANT(0, KIND_TNN, 8, 3, 3, 4),
 };
 const GemmVariant kTbn[] = {
-    LB_VARIANT(KIND_TBN, 8, 1, 4, 8),
-    LB_VARIANT(KIND_TBN, 8, 2, 4, 8),
-    LB_VARIANT(KIND_TBN, 8, 4, 4, 4),
-    LB_VARIANT(KIND_TBN, 16, 4, 4, 4),
-    LB_VARIANT(KIND_TBN, 16, 8, 4, 4),
-    LB_VARIANT(KIND_TBN, 16, 8, 8, 4),
+    LB_VARIANT(1, KIND_TBN, 8, 1, 4, 8),
+    LB_VARIANT(2, KIND_TBN, 8, 2, 4, 8),
+    LB_VARIANT(3, KIND_TBN, 8, 4, 4, 4),
+    LB_VARIANT(0, KIND_TBN, 16, 4, 4, 4),
+    LB_VARIANT(0, KIND_TBN, 16, 8, 4, 4),
+    LB_VARIANT(0, KIND_TBN, 16, 8, 8, 4),
+    LB_VARIANT(0, KIND_TBN, 16, 2, 4, 8),
+    LB_VARIANT(0, KIND_TBN, 8, 4, 8, 4),
+    LB_VARIANT(0, KIND_TBN, 8, 4, 2, 4),
 };
 
 }  // namespace

@@ -22,6 +22,7 @@ struct GemmArgs {
 
 struct GemmVariant {
     const char *name;
+    int rank;          // preference of the shape-based selection, 0 = manual only
     int tileS, tileV;  // workgroup tile extents along S and V
     hipError_t (*launch)(const GemmArgs &);
     hipError_t (*launch_transposed)(const GemmArgs &);
