@@ -121,7 +121,9 @@ LB_API int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_
 
 /*
  * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
- *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn
+ *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
+ *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel,
+ *            4 = workgroup tile of gemm_i8_mfma
  *   variant  index into that op's variant table, or -1 to restore shape-based selection.
  * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
  * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).

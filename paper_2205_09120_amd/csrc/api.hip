@@ -27,6 +27,8 @@ int fail(int code, const char *fmt, ...)
 constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K must fit
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
+constexpr int64_t kSkinnyMax = 16;             // widest "skinny" side served by the depth-split kernel
+
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // rows*ceil(K/64)*unit with overflow detection; 0 on failure
@@ -122,6 +124,30 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
 
     int count = 0;
     const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
+    const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
+
+    // Skinny problems (fully connected layers with a small batch) stream the large operand once and split the
+    // depth across lanes.  A forced tile variant bypasses this path.
+    if (!forced) {
+        const bool skinny_n = N <= kSkinnyMax && M >= 64;
+        const bool skinny_m = !skinny_n && M <= kSkinnyMax && N >= 64 && kind != lowbit::KIND_TBN;
+        if (skinny_n || skinny_m) {
+            lowbit::SkinnyArgs sa;
+            sa.Xp = skinny_n ? Ap : Bp;
+            sa.Yp = skinny_n ? Bp : Ap;
+            sa.rowsX = (int)(skinny_n ? M : N);
+            sa.rowsY = (int)(skinny_n ? N : M);
+            sa.KW = (int)KW;
+            sa.K = (int)K;
+            sa.C = C;
+            sa.ldc = ldc;
+            sa.stream = static_cast<hipStream_t>(stream);
+            const hipError_t e = lowbit::launch_gemm_skinny(kind, sa, skinny_m);
+            if (e != hipSuccess)
+                return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+            return LB_OK;
+        }
+    }
     lowbit::GemmArgs a;
     bool transposed;
     if (kind == lowbit::KIND_TBN) {
@@ -152,9 +178,7 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     a.C = C;
     a.ldc = ldc;
     a.stream = static_cast<hipStream_t>(stream);
-    int v = g_forced[kind];
-    if (v < 0 || v >= count)
-        v = choose_variant(tab, count, a.rowsS, a.rowsV);
+    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV);
     const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -237,6 +261,18 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
 int lb_set_variant(int op, int variant)
 {
     int count = 0;
+    if (op == 4) {
+        if (variant < -1 || variant > 2)
+            return fail(LB_EINVAL, "lb_set_variant: int8 tile %d out of range", variant);
+        lowbit::i8_force_tile(variant);
+        return LB_OK;
+    }
+    if (op == 3) {
+        if (variant < -1 || variant >= lowbit::skinny_num_configs())
+            return fail(LB_EINVAL, "lb_set_variant: skinny config %d out of range", variant);
+        lowbit::skinny_force_config(variant);
+        return LB_OK;
+    }
     if (op < 0 || op > 2 || !lowbit::gemm_variants(op, &count))
         return fail(LB_EINVAL, "lb_set_variant: op=%d out of range", op);
     if (variant < -1 || variant >= count)
@@ -248,6 +284,10 @@ int lb_set_variant(int op, int variant)
 int lb_num_variants(int op)
 {
     int count = 0;
+    if (op == 3)
+        return lowbit::skinny_num_configs();
+    if (op == 4)
+        return 3;
     if (op < 0 || op > 2)
         return 0;
     lowbit::gemm_variants(op, &count);

@@ -30,6 +30,21 @@ struct GemmVariant {
 
 const GemmVariant *gemm_variants(int kind, int *count);
 
+// Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8
+// strings at a time).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.
+// Operand classes per kind: BNN X,Y binary; TNN X,Y ternary; TBN X ternary, Y binary.
+struct SkinnyArgs {
+    const void *Xp;
+    const void *Yp;
+    int rowsX, rowsY, KW, K;
+    int32_t *C;
+    int64_t ldc;
+    hipStream_t stream;
+};
+hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed);
+int skinny_num_configs();
+void skinny_force_config(int cfg);  // -1 = shape-based
+
 // Packing launchers (pack.hip).  Element (r,k) = src[r*stride_r + k*stride_k].
 hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
                        uint64_t *dst, hipStream_t stream);
@@ -37,5 +52,6 @@ hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K,
 // int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream);
+void i8_force_tile(int t);  // -1 = shape-based, 0 = 128x128, 1 = 256x256, 2 = 256x128
 
 }  // namespace lowbit

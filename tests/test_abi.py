@@ -94,7 +94,11 @@ def test_variant_hooks(L):
         assert L.lb_set_variant(op, n) == binding.LB_EINVAL
         assert L.lb_set_variant(op, n - 1) == binding.LB_OK
         assert L.lb_set_variant(op, -1) == binding.LB_OK
-    assert L.lb_set_variant(3, 0) == binding.LB_EINVAL
+    assert L.lb_num_variants(3) >= 1 and L.lb_set_variant(3, 0) == binding.LB_OK
+    assert L.lb_set_variant(3, -1) == binding.LB_OK
+    assert L.lb_set_variant(3, L.lb_num_variants(3)) == binding.LB_EINVAL
+    assert L.lb_set_variant(4, 0) == binding.LB_OK and L.lb_set_variant(4, -1) == binding.LB_OK
+    assert L.lb_set_variant(5, 0) == binding.LB_EINVAL
     assert L.lb_num_variants(7) == 0
 
 

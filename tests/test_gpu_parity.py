@@ -156,6 +156,20 @@ def test_gemm_edge_shapes_all_variants(kind):
         lb.lb_set_variant(kind, -1)
 
 
+SKINNY_SHAPES = [(64, 1, 64), (64, 8, 1), (100, 9, 16384 + 70), (4096, 16, 300), (1000, 3, 20000), (3, 1000, 700),
+                 (16, 64, 16385), (8, 4100, 130), (257, 8, 16384), (5000, 7, 65)]
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_skinny_shapes(kind):
+    """Shapes with one narrow side take the depth-split kernel (both orientations, several depth chunks, tails)."""
+    for (M, N, K) in SKINNY_SHAPES:
+        say(f"gemm_{kind} skinny M={M} N={N} K={K}")
+        A, B = synth.make_custom(kind, M, N, K, seed=M + 5 * N + 11 * K)
+        got = run_gemm(kind, A, B).cpu().numpy()
+        assert np.array_equal(got, oracle.gemm(A, B)), (M, N, K)
+
+
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
 def test_gemm_ldc_and_untouched_padding(kind):
     M, N, K, ldc = 37, 50, 333, 64
@@ -199,15 +213,21 @@ def test_deterministic():
 # ------------------------------------------------------------------------------------------------ int8 matrix-core comparator
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (128, 128, 64), (257, 300, 1000),
-                                   (512, 784, 2304), (33, 8, 4096)])
+                                   (512, 784, 2304), (33, 8, 4096), (300, 515, 131), (256, 256, 64)])
 def test_i8_mfma(M, N, K):
     say(f"gemm_i8_mfma M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
     A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
     B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
-    got = lb.gemm_i8_mfma(M, N, K, dev(A), K, dev(B), N)
-    torch.cuda.synchronize()
-    assert np.array_equal(got.cpu().numpy(), oracle.gemm(A, B))
+    want = oracle.gemm(A, B)
+    try:
+        for tile in (-1, 0, 1, 2):
+            lb.lb_set_variant(4, tile)
+            got = lb.gemm_i8_mfma(M, N, K, dev(A), K, dev(B), N)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want), tile
+    finally:
+        lb.lb_set_variant(4, -1)
 
 
 def test_i8_mfma_on_ternary_config():
