@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "lowbit_internal.h"
 
 namespace lowbit {
@@ -72,7 +74,14 @@ __device__ __forceinline__ void popc_acc(int32_t &acc, uint32_t x)
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
 }
 
-template <int KIND, int TS, int TV, int WAVES, int KG, bool TR>
+// SG depth words of an S string fetched by one scalar load (SG*SD dwords, at most 16).  Large tiles use SG = 1;
+// the small, latency-bound tiles fetch up to 16 dwords per string at once so that a wave waits for scalar memory
+// once per SG depth words instead of once per word.
+template <int N> struct alignas(4) Words { uint32_t w[N]; };
+
+template <int N> using IntC = std::integral_constant<int, N>;
+
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
 __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
                                                                const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
                                                                int KW, int K, int32_t *__restrict__ C, int64_t ldc,
@@ -162,7 +171,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         if (c + 1 < nchunks)
             fetch(kg0 + KG);
         const int gmax = (KW - kg0) < KG ? (KW - kg0) : KG;
-        for (int g = 0; g < gmax; ++g) {
+        auto body1 = [&](int g) __attribute__((always_inline)) {
             SVec sv[TS];
 #pragma unroll
             for (int i = 0; i < TS; ++i)
@@ -207,7 +216,76 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                     }
                 }
             }
+        };
+        // SG depth words at a time: all scalar loads and all LDS reads of the batch are issued before the first use
+        auto bodyN = [&](auto sgc, int g) __attribute__((always_inline)) {
+            constexpr int SGN = decltype(sgc)::value;
+            constexpr int NW = SGN * SD;
+            static_assert(NW <= 16, "a scalar load fetches at most 16 dwords");
+            Words<NW> sw[TS];
+#pragma unroll
+            for (int i = 0; i < TS; ++i)
+                sw[i] = *reinterpret_cast<const Words<NW> *>(srow[i] + kg0 + g);
+            VVec b[SGN][TV];
+#pragma unroll
+            for (int q = 0; q < SGN; ++q)
+#pragma unroll
+                for (int t = 0; t < TV; ++t)
+                    b[q][t] = lds[buf][(g + q) * STRIDE + t * 64 + lane];
+#pragma unroll
+            for (int q = 0; q < SGN; ++q)
+#pragma unroll
+                for (int t = 0; t < TV; ++t) {
+                    const VVec bb = b[q][t];
+                    if constexpr (KIND == KIND_BNN) {
+#pragma unroll
+                        for (int i = 0; i < TS; ++i) {
+                            popc_acc(acc[0][i][t], xor_sv(sw[i].w[q * 2], bb.x));
+                            popc_acc(acc[0][i][t], xor_sv(sw[i].w[q * 2 + 1], bb.y));
+                        }
+                    } else if constexpr (KIND == KIND_TNN) {
+#pragma unroll
+                        for (int i = 0; i < TS; ++i) {
+                            const uint32_t p0 = sw[i].w[q * 4], p1 = sw[i].w[q * 4 + 1];
+                            const uint32_t n0 = sw[i].w[q * 4 + 2], n1 = sw[i].w[q * 4 + 3];
+                            const uint32_t m0 = and_sv(p0 | n0, bb.x), m1 = and_sv(p1 | n1, bb.y);
+                            const uint32_t u0 = xor_and_svv(n0, bb.z, m0), u1 = xor_and_svv(n1, bb.w, m1);
+                            popc_acc(acc[0][i][t], m0);
+                            popc_acc(acc[1][i][t], u0);
+                            popc_acc(acc[0][i][t], m1);
+                            popc_acc(acc[1][i][t], u1);
+                        }
+                    } else {
+                        popc_acc(nnz[t], bb.x);
+                        popc_acc(nnz[t], bb.y);
+#pragma unroll
+                        for (int i = 0; i < TS; ++i) {
+                            popc_acc(acc[0][i][t], xor_and_svv(sw[i].w[q * 2], bb.z, bb.x));
+                            popc_acc(acc[0][i][t], xor_and_svv(sw[i].w[q * 2 + 1], bb.w, bb.y));
+                        }
+                    }
+                }
+        };
+        // batches of SG depth words, then the remainder in halving batch sizes, then single words
+        int g = 0;
+        if constexpr (SG > 1) {
+            for (; g + SG <= gmax; g += SG)
+                bodyN(IntC<SG>{}, g);
+            if constexpr (SG >= 8) {
+                if (g + 4 <= gmax) {
+                    bodyN(IntC<4>{}, g);
+                    g += 4;
+                }
+            }
+            if constexpr (SG >= 4) {
+                if (g + 2 <= gmax) {
+                    bodyN(IntC<2>{}, g);
+                    g += 2;
+                }
+            }
         }
+        for (; g < gmax; ++g)
+            body1(g);
         if (c + 1 < nchunks)
             commit(buf ^ 1);
         __syncthreads();
@@ -252,7 +330,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
     }
 }
 
-template <int KIND, int TS, int TV, int WAVES, int KG, bool TR>
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
 hipError_t launch(const GemmArgs &a)
 {
     const int nSB = (a.rowsS + WAVES * TS - 1) / (WAVES * TS);
@@ -262,52 +340,47 @@ hipError_t launch(const GemmArgs &a)
     const int64_t grid = (int64_t)tiles_per_xcd * 8;
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
+    hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, SG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
                        a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd);
     return hipGetLastError();
 }
 
-#define LB_VARIANT(RANK, KIND, TS, TV, WAVES, KG)                                                   \
-    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG, RANK, TS * WAVES, 64 * TV,                     \
-     &launch<KIND, TS, TV, WAVES, KG, false>, &launch<KIND, TS, TV, WAVES, KG, true>}
+#define LB_VARIANT(RANK, KIND, TS, TV, WAVES, KG, SG)                                               \
+    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, RANK, TS * WAVES, 64 * TV,           \
+     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>}
 
-// rank: preference of the shape-based selection (higher wins among the variants that yield enough workgroups;
-// 0 = only reachable through lb_set_variant)
+// rank: preference of the shape-based selection (the highest rank wins among the variants that yield enough
+// workgroups, otherwise the ranked variant with the most workgroups; 0 = only reachable through lb_set_variant).
+// The first row of each table is the small-problem instance: 4 x 64 outputs per wave and scalar loads of 16 dwords.
 const GemmVariant kBnn[] = {
-    LB_VARIANT(1, KIND_BNN, 8, 1, 4, 8),
-    LB_VARIANT(2, KIND_BNN, 8, 2, 4, 8),
-    LB_VARIANT(3, KIND_BNN, 8, 4, 4, 8),
-    LB_VARIANT(0, KIND_BNN, 8, 8, 4, 4),
-    LB_VARIANT(0, KIND_BNN, 16, 4, 4, 8),
-    LB_VARIANT(0, KIND_BNN, 16, 8, 4, 4),
-    LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8),
-    LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8),
-    LB_VARIANT(0, KIND_BNN, 8, 4, 2, 8),
+    LB_VARIANT(1, KIND_BNN, 4, 1, 4, 16, 8),
+    LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 1),
+    LB_VARIANT(3, KIND_BNN, 8, 2, 4, 8, 1),
+    LB_VARIANT(4, KIND_BNN, 8, 4, 4, 8, 1),
+    LB_VARIANT(5, KIND_BNN, 16, 2, 4, 8, 1),
+    LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8, 1),
+    LB_VARIANT(0, KIND_BNN, 8, 1, 4, 8, 4),
+    LB_VARIANT(0, KIND_BNN, 2, 1, 4, 16, 8),
 };
 const GemmVariant kTnn[] = {
-    LB_VARIANT(1, KIND_TNN, 8, 1, 4, 8),
-    LB_VARIANT(2, KIND_TNN, 8, 2, 4, 8),
-    LB_VARIANT(3, KIND_TNN, 8, 4, 4, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 8, 4, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 8, 8, 4),
-    LB_VARIANT(0, KIND_TNN, 4, 8, 8, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 4, 4, 8),
-    LB_VARIANT(0, KIND_TNN, 8, 4, 2, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 6, 4, 4),
-    LB_VARIANT(0, KIND_TNN, 12, 4, 4, 4),
-    LB_VARIANT(0, KIND_TNN, 8, 3, 3, 4),
+    LB_VARIANT(1, KIND_TNN, 4, 1, 4, 16, 4),
+    LB_VARIANT(2, KIND_TNN, 8, 1, 4, 8, 1),
+    LB_VARIANT(3, KIND_TNN, 8, 2, 4, 8, 1),
+    LB_VARIANT(4, KIND_TNN, 8, 4, 4, 4, 1),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4, 1),
+    LB_VARIANT(0, KIND_TNN, 12, 4, 4, 4, 1),
+    LB_VARIANT(0, KIND_TNN, 8, 1, 4, 8, 2),
+    LB_VARIANT(0, KIND_TNN, 2, 1, 4, 16, 4),
 };
 const GemmVariant kTbn[] = {
-    LB_VARIANT(1, KIND_TBN, 8, 1, 4, 8),
-    LB_VARIANT(2, KIND_TBN, 8, 2, 4, 8),
-    LB_VARIANT(3, KIND_TBN, 8, 4, 4, 4),
-    LB_VARIANT(0, KIND_TBN, 16, 4, 4, 4),
-    LB_VARIANT(0, KIND_TBN, 16, 8, 4, 4),
-    LB_VARIANT(0, KIND_TBN, 16, 8, 8, 4),
-    LB_VARIANT(0, KIND_TBN, 16, 2, 4, 8),
-    LB_VARIANT(0, KIND_TBN, 8, 4, 8, 4),
-    LB_VARIANT(0, KIND_TBN, 8, 4, 2, 4),
+    LB_VARIANT(1, KIND_TBN, 4, 1, 4, 16, 8),
+    LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 1),
+    LB_VARIANT(3, KIND_TBN, 8, 2, 4, 8, 1),
+    LB_VARIANT(4, KIND_TBN, 8, 4, 4, 4, 1),
+    LB_VARIANT(5, KIND_TBN, 8, 4, 8, 4, 1),
+    LB_VARIANT(0, KIND_TBN, 16, 4, 4, 4, 1),
+    LB_VARIANT(0, KIND_TBN, 8, 1, 4, 8, 4),
+    LB_VARIANT(0, KIND_TBN, 2, 1, 4, 16, 8),
 };
 
 }  // namespace

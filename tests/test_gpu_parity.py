@@ -137,7 +137,7 @@ def test_gemm_headline_full_size():
 
 # ------------------------------------------------------------------------------------------------ GEMM, edge shapes, all variants
 
-EDGE_SHAPES = [(1, 1, 1), (1, 1, 64), (1, 70, 65), (70, 1, 63), (5, 7, 130), (33, 65, 64), (64, 64, 128),
+EDGE_SHAPES = [(70, 70, 40 * 64 + 1), (1, 1, 1), (1, 1, 64), (1, 70, 65), (70, 1, 63), (5, 7, 130), (33, 65, 64), (64, 64, 128),
                (65, 129, 200), (100, 300, 577), (8, 520, 1000), (130, 8, 2000), (257, 513, 320)]
 
 
