@@ -31,6 +31,54 @@ HBM_PEAK_GBS = 8000.0
 LANE_INSTR = {"tnn": 4, "tbn": 2, "bnn": 2}
 
 
+def trace_scenario(args, torch, lb, synth) -> int:
+    """Launch patterns meant to be run under `rocprofv3 --kernel-trace`; the trace, not this process, is the result.
+
+    skinny: for cfg5 (TNN, TBN, BNN) two rounds over 384 MiB worth of copies of the packed large operand (24
+            ternary / 48 binary copies: every launch streams it from HBM, cold), then 24 launches on one copy
+            (warm), per skinny configuration.
+    small:  for cfg1, cfg2, cfg3 30 launches per tile variant of the tiled kernel.
+    """
+    if args.scenario == "skinny":
+        for name in ("cfg5_tnn_fc_n8", "cfg5_tbn_fc_n8", "cfg5_bnn_fc_n8"):
+            w = synth.WORKLOADS[name]
+            ncopy = 48 if w.kind == "bnn" else 24
+            A, B = synth.make_inputs(w)
+            Ap = lb.pack_a(w.kind, torch.from_numpy(A).cuda())
+            Bp = lb.pack_b(w.kind, torch.from_numpy(B).cuda())
+            copies = [Ap.clone() for _ in range(ncopy)]
+            C = torch.empty((w.M, w.N), dtype=torch.int32, device="cuda")
+            torch.cuda.synchronize()
+            for cfg in (range(lb.lb_num_variants(3)) if args.all_variants else [-1]):
+                lb.lb_set_variant(3, cfg)
+                for i in range(2 * ncopy):
+                    lb.gemm(w.kind, w.M, w.N, w.K, copies[i % ncopy], Bp, C, w.N)
+                torch.cuda.synchronize()
+                for i in range(24):
+                    lb.gemm(w.kind, w.M, w.N, w.K, copies[0], Bp, C, w.N)
+                torch.cuda.synchronize()
+            lb.lb_set_variant(3, -1)
+            print(f"{name}: traced", flush=True)
+    else:
+        for name in ("cfg1_tnn_conv3x3x64_16x16", "cfg2_bnn_conv3x3x128_56x56", "cfg3_tbn_conv3x3x256_28x28"):
+            w = synth.WORKLOADS[name]
+            A, B = synth.make_inputs(w)
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+            Ap, Bp = lb.pack_a(w.kind, dA), lb.pack_b(w.kind, dB)
+            C = torch.empty((w.M, w.N), dtype=torch.int32, device="cuda")
+            torch.cuda.synchronize()
+            for v in (list(range(lb.lb_num_variants(w.kind))) if args.all_variants else []) + [-1]:
+                lb.lb_set_variant(w.kind, v)
+                for _ in range(30):
+                    lb.gemm(w.kind, w.M, w.N, w.K, Ap, Bp, C, w.N)
+                torch.cuda.synchronize()
+            for _ in range(30):
+                lb.gemm_i8_mfma(w.M, w.N, w.K, dA, w.K, dB, w.N, C, w.N)
+            torch.cuda.synchronize()
+            print(f"{name}: traced", flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +86,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scenario", choices=["headline", "skinny", "small"], default="headline",
+                    help="headline: the benchmark proper.  skinny / small: launch patterns for rocprofv3 kernel traces "
+                         "(cfg5 cold/warm per skinny configuration; cfg1-3 per tile variant); they print no metric")
+    ap.add_argument("--all-variants", action="store_true", help="with --scenario: loop over every kernel variant")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM bytes) so that profiler byte counters "
                          "collected over this command can be scaled")
@@ -55,6 +107,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     lb.lib()  # raises if the HIP library is missing
+
+    if args.scenario != "headline":
+        return trace_scenario(args, torch, lb, synth)
 
     w = synth.WORKLOADS[synth.HEADLINE]
     A, B = synth.make_inputs(w)
@@ -186,7 +241,7 @@ def main() -> int:
             cold = None
             if name.startswith("cfg5_"):
                 # cold operand: rotate over enough copies of packed A to exceed the 256 MB last-level cache
-                ncopy = 24 if ww.kind != "bnn" else 40
+                ncopy = 24 if ww.kind != "bnn" else 48
                 copies = [ap_.clone() for _ in range(ncopy)]
                 it = iter(range(10 ** 9))
                 cold = graph_time(lambda: lb.gemm(ww.kind, ww.M, ww.N, ww.K, copies[next(it) % ncopy], bp_, c_, ww.N),
