@@ -226,6 +226,14 @@ def main() -> int:
         ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
         extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
         extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
+        # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
+        try:
+            torch._int_mm(dA, dB)
+            tlib = dev_time(lambda: torch._int_mm(dA, dB), 10)
+            extra["library_int8_gemm_tops"] = w.ops / tlib / 1e12
+        except Exception as e:  # not available on every build
+            extra["library_int8_gemm_tops"] = None
+            extra["library_int8_gemm_error"] = str(e)[:120]
         others = {}
         del dB, Bp, C
         for name, ww in synth.WORKLOADS.items():
