@@ -171,6 +171,17 @@ def test_gemm_skinny_shapes(kind):
 
 
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_paper_shape_grid(kind):
+    """All 64 height x width x depth shapes of the paper's timing experiment (Section IV-B)."""
+    for idx, (H, W, D) in enumerate(synth.paper_shape_grid()):
+        if idx % 8 == 0:
+            say(f"gemm_{kind} paper grid shapes {idx}..{idx + 7}: first {H}x{W}x{D}")
+        A, B = synth.make_custom(kind, H, W, D, seed=1000 + idx)
+        got = run_gemm(kind, A, B).cpu().numpy()
+        assert np.array_equal(got, oracle.gemm(A, B)), (H, W, D)
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
 def test_gemm_ldc_and_untouched_padding(kind):
     M, N, K, ldc = 37, 50, 333, 64
     say(f"gemm_{kind} ldc M={M} N={N} K={K} ldc={ldc}")
