@@ -287,6 +287,24 @@ def main() -> int:
         except Exception as e:  # not available on every build
             extra["library_int8_gemm_tops"] = None
             extra["library_int8_gemm_error"] = str(e)[:120]
+        # convolution lowering on packed words: the same right operand built from a channel-packed 16x56x56x512
+        # feature map (pack the map, gather words) instead of packing the unrolled 4608 x 50176 int8 matrix
+        nb, FH, FW, FC = 16, 56, 56, 512
+        fmap = torch.from_numpy(synth.draw_ternary(np.random.default_rng(w.seed), (nb * FH * FW, FC), w.p0_b)).cuda()
+        Fp = torch.empty(lb.packed_ternary_bytes(nb * FH * FW, FC) // 8, dtype=torch.int64, device="cuda")
+
+        def conv_step():
+            lb.pack_ternary(dA, M, K, K, 1, Ap)
+            lb.pack_ternary(fmap, nb * FH * FW, FC, FC, 1, Fp)
+            lb.im2col_packed(Fp, 2, nb, FH, FW, FC, 3, 3, 1, 1, 1, 1, Bp)
+            lb.gemm_tnn(M, N, K, Ap, Bp, C, N)
+
+        tfm = dev_time(lambda: lb.pack_ternary(fmap, nb * FH * FW, FC, FC, 1, Fp), 50)
+        tic = dev_time(lambda: lb.im2col_packed(Fp, 2, nb, FH, FW, FC, 3, 3, 1, 1, 1, 1, Bp), 50)
+        tcs = dev_time(conv_step, 50)
+        extra["conv_lowering_on_packed_words"] = {"pack_feature_map_us": tfm * 1e6, "im2col_packed_us": tic * 1e6,
+                                                  "step_ms": tcs * 1e3, "step_tops": w.ops / tcs / 1e12}
+        del fmap, Fp
         others = {}
         del dB, Bp, C
         for name, ww in synth.WORKLOADS.items():

@@ -89,6 +89,27 @@ LB_API int pack_ternary(const int8_t *src, int64_t rows, int64_t K, int64_t stri
                  void *stream);
 
 /*
+ * im2col_packed -- lower a convolution to the GEMM above without unrolling the int8 feature map: gather the packed
+ * right operand (one bit string per output pixel) from a feature map that is already packed along its channels.
+ * The paper computes convolutions as matrix products after an im2col unrolling (Section I; Section IV-A and eq. (5):
+ * depth = H_k * W_k * C_in); this call does that unrolling on packed words.
+ *
+ *   Fp        device, packed feature map: batch*H*W bit strings (pixels in NHWC order) of depth C, i.e. the output of
+ *             pack_binary / pack_ternary(fmap, rows = batch*H*W, K = C, stride_r = C, stride_k = 1).
+ *   planes    1 = binary strings, 2 = ternary strings (plus and minus word adjacent).
+ *   C         channels; must be a multiple of 64 (LB_EUNSUPPORTED otherwise: unroll the int8 map and use pack_*).
+ *   kh, kw    window; stride_h/w >= 1; pad_h/w >= 0 (zero padding).
+ *   Bp        device, out: N = batch*OH*OW bit strings of depth K = kh*kw*C with OH = (H + 2*pad_h - kh)/stride_h + 1,
+ *             OW likewise; string n = (b*OH + oy)*OW + ox; depth index (ky*kw + kx)*C + c.  Size
+ *             packed_binary_bytes(N, K) or packed_ternary_bytes(N, K).  Positions in the padding are zero words:
+ *             the ternary value 0, or the binary value +1 (a binary map cannot represent 0).
+ * The matching left operand holds one filter per row with the same (ky, kx, c) depth order.
+ * An empty problem (batch == 0, or a window larger than the padded map) is a valid no-op.
+ */
+LB_API int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int64_t W, int64_t C, int kh, int kw,
+                         int stride_h, int stride_w, int pad_h, int pad_w, uint64_t *Bp, void *stream);
+
+/*
  * gemm_bnn -- binary x binary, eq. (6):  C[i][j] = K - 2 * sum_w popcount(Ap[i][w] xor Bp[j][w]).
  * gemm_tnn -- ternary x ternary, eq. (7) with the ternary product of Section III-A (Table I, columns z+, z-).
  * gemm_tbn -- ternary A x binary B, eq. (7) with the ternary-binary product (Table I, columns u+, u-).

@@ -20,7 +20,7 @@ OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
 _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
-           "pack_ternary", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_i8_mfma", "lb_set_variant", "lb_num_variants",
+           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_i8_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name")
 
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         for f in (L.gemm_bnn, L.gemm_tnn, L.gemm_tbn):
             f.restype = ci
             f.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
+        L.im2col_packed.restype = ci
+        L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
         L.gemm_i8_mfma.restype = ci
         L.gemm_i8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
         L.lb_set_variant.restype = ci
@@ -115,6 +117,20 @@ def pack_ternary(src: torch.Tensor, rows: int, K: int, stride_r: int, stride_k: 
                  dst: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """Returns dst (int64 words, rows*ceil(K/64)*2: plus word, minus word, ...)."""
     return _pack(lib().pack_ternary, packed_ternary_bytes, src, rows, K, stride_r, stride_k, dst, stream)
+
+
+def im2col_packed(Fp: torch.Tensor, planes: int, batch: int, H: int, W: int, C: int, kh: int, kw: int,
+                  stride_h: int = 1, stride_w: int = 1, pad_h: int = 0, pad_w: int = 0,
+                  Bp: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Packed right operand (batch*OH*OW strings of depth kh*kw*C) gathered from a channel-packed feature map."""
+    if Bp is None:
+        OH = (H + 2 * pad_h - kh) // stride_h + 1 if H + 2 * pad_h >= kh else 0
+        OW = (W + 2 * pad_w - kw) // stride_w + 1 if W + 2 * pad_w >= kw else 0
+        words = batch * OH * OW * kh * kw * (C // 64) * planes
+        Bp = torch.empty(max(words, 0), dtype=torch.int64, device=Fp.device)
+    _check(lib().im2col_packed(_ptr(Fp), planes, batch, H, W, C, kh, kw, stride_h, stride_w, pad_h, pad_w, _ptr(Bp),
+                               _stream(stream)))
+    return Bp
 
 
 def _gemm(fn, M, N, K, Ap, Bp, C, ldc, stream):

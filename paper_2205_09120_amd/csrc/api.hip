@@ -258,6 +258,54 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
     return LB_OK;
 }
 
+int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int64_t W, int64_t C, int kh, int kw,
+                  int stride_h, int stride_w, int pad_h, int pad_w, uint64_t *Bp, void *stream)
+{
+    const char *name = "im2col_packed";
+    if (planes != 1 && planes != 2)
+        return fail(LB_EINVAL, "%s: planes=%d must be 1 (binary) or 2 (ternary)", name, planes);
+    if (batch < 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0)
+        return fail(LB_EINVAL, "%s: bad geometry batch=%lld H=%lld W=%lld C=%lld window %dx%d stride %dx%d pad %dx%d",
+                    name, (long long)batch, (long long)H, (long long)W, (long long)C, kh, kw, stride_h, stride_w, pad_h,
+                    pad_w);
+    if (C % 64 != 0)
+        return fail(LB_EUNSUPPORTED, "%s: C=%lld is not a multiple of 64", name, (long long)C);
+    constexpr int64_t kLim = 1 << 24;  // keeps every product below in 64 bits and the map extents in 32
+    if (H > kLim || W > kLim || C > kLim * 64 || kh > 4096 || kw > 4096 || stride_h > kLim || stride_w > kLim ||
+        pad_h > kLim || pad_w > kLim || batch > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: geometry too large", name);
+    const int64_t OH = (H + 2 * pad_h - kh) >= 0 ? (H + 2 * pad_h - kh) / stride_h + 1 : 0;
+    const int64_t OW = (W + 2 * pad_w - kw) >= 0 ? (W + 2 * pad_w - kw) / stride_w + 1 : 0;
+    if (batch == 0 || OH == 0 || OW == 0)
+        return LB_OK;
+    const int64_t CW = C / 64;
+    const int64_t kwout = (int64_t)kh * kw * CW;
+    if (kwout > kMaxExtent || OH * OW > kMaxExtent || batch > INT64_MAX / (OH * OW) / kwout / 16)
+        return fail(LB_EOVERFLOW, "%s: packed operand too large", name);
+    if (!Fp || !Bp)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (!aligned(Fp, 16) || !aligned(Bp, 16))
+        return fail(LB_EINVAL, "%s: operands must be 16-byte aligned", name);
+    lowbit::Im2colGeom g;
+    g.batch = batch;
+    g.H = (int)H;
+    g.W = (int)W;
+    g.CW = (int)CW;
+    g.OH = (int)OH;
+    g.OW = (int)OW;
+    g.kh = kh;
+    g.kw = kw;
+    g.sh = stride_h;
+    g.sw = stride_w;
+    g.ph = pad_h;
+    g.pw = pad_w;
+    const hipError_t e = lowbit::launch_im2col_packed(planes, Fp, Bp, g, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
 int lb_set_variant(int op, int variant)
 {
     int count = 0;

@@ -49,6 +49,14 @@ void skinny_force_config(int cfg);  // -1 = shape-based
 hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
                        uint64_t *dst, hipStream_t stream);
 
+// Packed-domain im2col (im2col.hip).  CW = channel words (C/64); OH, OW are the output map extents.
+struct Im2colGeom {
+    int64_t batch;
+    int H, W, CW, OH, OW;
+    int kh, kw, sh, sw, ph, pw;
+};
+hipError_t launch_im2col_packed(int planes, const uint64_t *Fp, uint64_t *Bp, const Im2colGeom &g, hipStream_t stream);
+
 // int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream);

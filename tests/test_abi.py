@@ -84,6 +84,20 @@ def test_i8_argument_validation(L):
     assert f(0, 4, 16, None, 16, None, 4, None, 4, None) == binding.LB_OK
 
 
+def test_im2col_argument_validation(L):
+    fake = 0x1000
+    f = L.im2col_packed
+    assert f(fake, 3, 1, 8, 8, 64, 3, 3, 1, 1, 1, 1, fake, None) == binding.LB_EINVAL          # planes
+    assert f(fake, 2, 1, 8, 8, 64, 3, 3, 0, 1, 1, 1, fake, None) == binding.LB_EINVAL          # stride 0
+    assert f(fake, 2, 1, 8, 8, 64, 3, 3, 1, 1, -1, 1, fake, None) == binding.LB_EINVAL         # negative padding
+    assert f(fake, 2, 1, 8, 8, 72, 3, 3, 1, 1, 1, 1, fake, None) == binding.LB_EUNSUPPORTED    # C % 64 != 0
+    assert f(None, 2, 1, 8, 8, 64, 3, 3, 1, 1, 1, 1, fake, None) == binding.LB_EINVAL
+    assert f(fake, 2, 1, 8, 8, 64, 3, 3, 1, 1, 1, 1, fake + 8, None) == binding.LB_EINVAL      # misaligned
+    assert f(None, 2, 0, 8, 8, 64, 3, 3, 1, 1, 1, 1, None, None) == binding.LB_OK              # empty batch
+    assert f(None, 1, 4, 2, 2, 64, 5, 5, 1, 1, 0, 0, None, None) == binding.LB_OK              # window larger than map
+    assert f(fake, 2, 1, 1 << 25, 8, 64, 3, 3, 1, 1, 1, 1, fake, None) == binding.LB_EOVERFLOW
+
+
 def test_variant_hooks(L):
     for op in range(3):
         n = L.lb_num_variants(op)

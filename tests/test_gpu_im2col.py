@@ -1,0 +1,107 @@
+"""GPU parity for the packed-domain im2col and the convolution it feeds (bit-exact against the CPU oracles)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import bitref, oracle
+from oracle import im2col as oi
+from paper_2205_09120_amd import binding as lb
+from paper_2205_09120_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def words(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+GEOMS = [  # batch, H, W, C, kh, kw, sh, sw, ph, pw
+    (1, 5, 6, 64, 3, 3, 1, 1, 1, 1),
+    (2, 7, 5, 128, 3, 2, 2, 1, 0, 1),
+    (3, 4, 4, 192, 1, 1, 1, 1, 0, 0),
+    (2, 9, 8, 64, 5, 3, 2, 3, 2, 1),
+    (1, 3, 3, 64, 3, 3, 1, 1, 0, 0),
+    (2, 6, 6, 256, 2, 2, 2, 2, 1, 0),
+]
+
+
+def _fmap(kind, geom, seed):
+    nb, H, W, C = geom[:4]
+    X, _ = synth.make_custom(kind, nb * H * W, 1, C, seed)              # (pixels, C) with the kind's value set
+    return X.reshape(nb, H, W, C)
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("ternary", [True, False])
+def test_im2col_packed_matches_reference(geom, ternary):
+    nb, H, W, C, kh, kw, sh, sw, ph, pw = geom
+    say(f"im2col_packed geom={geom} ternary={ternary}")
+    fmap = _fmap("tnn" if ternary else "bnn", geom, seed=sum(geom))
+    d = torch.from_numpy(fmap).cuda()
+    pack = lb.pack_ternary if ternary else lb.pack_binary
+    Fp = pack(d, nb * H * W, C, C, 1)
+    Bp = lb.im2col_packed(Fp, 2 if ternary else 1, nb, H, W, C, kh, kw, sh, sw, ph, pw)
+    torch.cuda.synchronize()
+    B = oi.im2col(fmap, kh, kw, sh, sw, ph, pw)                          # (K, N) int8, zero padded
+    Bt = np.ascontiguousarray(B.T)
+    if ternary:
+        want = bitref.pack_ternary(Bt)
+    else:
+        # zero padding has no binary code; the library writes bit 0 (= +1) there, which is what the reference
+        # packer produces for a zero entry (x < 0 is false)
+        want = bitref.pack_binary(Bt)
+    assert np.array_equal(words(Bp), want.reshape(-1))
+
+
+@pytest.mark.parametrize("geom", GEOMS[:4])
+def test_convolution_through_im2col_packed(geom):
+    """Filters (ternary) x feature map (ternary): gemm_tnn on the gathered operand equals the direct convolution."""
+    nb, H, W, C, kh, kw, sh, sw, ph, pw = geom
+    say(f"conv via im2col_packed + gemm_tnn geom={geom}")
+    F = 37
+    fmap = _fmap("tnn", geom, seed=7 + sum(geom))
+    filt, _ = synth.make_custom("tnn", F, 1, kh * kw * C, seed=11)
+    OH, OW = oi.out_size(H, W, kh, kw, sh, sw, ph, pw)
+    N, K = nb * OH * OW, kh * kw * C
+    Ap = lb.pack_a("tnn", torch.from_numpy(filt).cuda())
+    Fp = lb.pack_ternary(torch.from_numpy(fmap).cuda(), nb * H * W, C, C, 1)
+    Bp = lb.im2col_packed(Fp, 2, nb, H, W, C, kh, kw, sh, sw, ph, pw)
+    Cm = lb.gemm_tnn(F, N, K, Ap, Bp)
+    torch.cuda.synchronize()
+    got = Cm.cpu().numpy().reshape(F, nb, OH, OW).transpose(1, 2, 3, 0)
+    want = oi.conv2d_direct(fmap, filt.reshape(F, kh, kw, C), sh, sw, ph, pw)
+    assert np.array_equal(got, want)
+
+
+def test_im2col_packed_headline_geometry():
+    """Batch 16 of 56x56x512 maps, 3x3 window, padding 1: the geometry behind the 4608 x 50176 benchmark operand.
+    Checked on sampled output strings (every tap, including padded borders) against the reference."""
+    nb, H, W, C, kh, kw = 16, 56, 56, 512, 3, 3
+    say("im2col_packed headline geometry 16x56x56x512, 3x3, pad 1")
+    rng = np.random.default_rng(5)
+    fmap = synth.draw_ternary(rng, (nb * H * W, C), 0.5).reshape(nb, H, W, C)
+    Fp = lb.pack_ternary(torch.from_numpy(fmap).cuda(), nb * H * W, C, C, 1)
+    Bp = lb.im2col_packed(Fp, 2, nb, H, W, C, kh, kw, 1, 1, 1, 1)
+    torch.cuda.synchronize()
+    got = words(Bp).reshape(nb * H * W, kh * kw * (C // 64), 2)
+    Fref = bitref.pack_ternary(fmap.reshape(-1, C)).reshape(nb, H, W, C // 64, 2)
+    pix = [(0, 0, 0), (0, 0, 55), (0, 55, 0), (15, 55, 55), (3, 17, 0), (7, 0, 31), (9, 28, 28)]
+    pix += [tuple(int(v) for v in p) for p in np.stack([rng.integers(0, nb, 200), rng.integers(0, H, 200),
+                                                         rng.integers(0, W, 200)], axis=1)]
+    for (b, oy, ox) in pix:
+        n = (b * H + oy) * W + ox
+        for ky in range(kh):
+            for kx in range(kw):
+                iy, ix = oy + ky - 1, ox + kx - 1
+                blk = got[n, (ky * kw + kx) * (C // 64):(ky * kw + kx + 1) * (C // 64)]
+                if 0 <= iy < H and 0 <= ix < W:
+                    assert np.array_equal(blk, Fref[b, iy, ix]), (b, oy, ox, ky, kx)
+                else:
+                    assert not blk.any(), (b, oy, ox, ky, kx)
