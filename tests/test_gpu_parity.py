@@ -248,3 +248,61 @@ def test_i8_mfma_on_ternary_config():
     got = lb.gemm_i8_mfma(w.M, w.N, w.K, dev(A), w.K, dev(B), w.N)
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy(), oracle.gemm(A, B))
+
+
+# ------------------------------------------------------------------------------------------------ streams, ldc on every path, random shapes
+
+def test_non_default_stream_and_overlap():
+    """Calls enqueue on the stream they are given: two problems on two streams, results checked after one sync."""
+    say("two streams")
+    A1, B1 = synth.make_custom("tnn", 300, 500, 900, seed=31)
+    A2, B2 = synth.make_custom("bnn", 200, 700, 1300, seed=32)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    dA1, dB1, dA2, dB2 = dev(A1), dev(B1), dev(A2), dev(B2)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s1):
+        C1 = lb.gemm("tnn", 300, 500, 900, lb.pack_a("tnn", dA1), lb.pack_b("tnn", dB1))
+    with torch.cuda.stream(s2):
+        C2 = lb.gemm("bnn", 200, 700, 1300, lb.pack_a("bnn", dA2, stream=s2), lb.pack_b("bnn", dB2, stream=s2),
+                     stream=s2)
+    torch.cuda.synchronize()
+    assert np.array_equal(C1.cpu().numpy(), oracle.gemm(A1, B1))
+    assert np.array_equal(C2.cpu().numpy(), oracle.gemm(A2, B2))
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+@pytest.mark.parametrize("shape", [(300, 8, 700), (9, 400, 260), (512, 70, 64)])
+def test_ldc_on_skinny_and_transposed_paths(kind, shape):
+    M, N, K = shape
+    ldc = N + 5
+    say(f"gemm_{kind} ldc={ldc} M={M} N={N} K={K}")
+    A, B = synth.make_custom(kind, M, N, K, seed=M + N + K)
+    C = torch.full((M, ldc), 12345, dtype=torch.int32, device="cuda")
+    run_gemm(kind, A, B, C=C, ldc=ldc)
+    got = C.cpu().numpy()
+    assert np.array_equal(got[:, :N], oracle.gemm(A, B))
+    assert np.all(got[:, N:] == 12345)
+
+
+def test_random_shapes():
+    """60 seeded random (kind, M, N, K) draws, log-uniform extents, through the shape-based dispatch."""
+    rng = np.random.default_rng(2024)
+    for it in range(60):
+        kind = ("bnn", "tnn", "tbn")[int(rng.integers(0, 3))]
+        M, N = (int(np.exp(rng.uniform(0, np.log(700)))) for _ in range(2))
+        K = int(np.exp(rng.uniform(0, np.log(5000))))
+        say(f"random shape {it}: gemm_{kind} M={M} N={N} K={K}")
+        A, B = synth.make_custom(kind, M, N, K, seed=5000 + it)
+        assert np.array_equal(run_gemm(kind, A, B).cpu().numpy(), oracle.gemm(A, B)), (kind, M, N, K)
+
+
+def test_sparse_and_dense_ternary_extremes():
+    """Ternary operands with P(0) = 0 and P(0) = 0.98 (and the all-zero operand on one side)."""
+    say("ternary density extremes")
+    for p0 in (0.0, 0.98):
+        A, B = synth.make_custom("tnn", 130, 260, 777, seed=int(p0 * 100) + 1, p0=p0)
+        assert np.array_equal(run_gemm("tnn", A, B).cpu().numpy(), oracle.gemm(A, B))
+        A, B = synth.make_custom("tbn", 130, 260, 777, seed=int(p0 * 100) + 2, p0=p0)
+        assert np.array_equal(run_gemm("tbn", A, B).cpu().numpy(), oracle.gemm(A, B))
+    A, B = synth.make_custom("tbn", 70, 90, 300, seed=3)
+    assert not run_gemm("tbn", np.zeros_like(A), B).cpu().numpy().any()
