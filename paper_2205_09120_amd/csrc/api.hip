@@ -77,10 +77,10 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
 }
 
 // Pick a tile variant: the highest-ranked one that still yields enough workgroups to occupy the 256 compute
-// units several times over; problems too small for that take the variant with the most workgroups.
+// units eight times over; problems too small for that take the variant with the most workgroups.
 int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV)
 {
-    constexpr int64_t kWanted = 256 * 6;
+    constexpr int64_t kWanted = 256 * 8;
     int best = -1, fallback = 0;
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {

@@ -354,33 +354,29 @@ hipError_t launch(const GemmArgs &a)
 // The first row of each table is the small-problem instance: 4 x 64 outputs per wave and scalar loads of 16 dwords.
 const GemmVariant kBnn[] = {
     LB_VARIANT(1, KIND_BNN, 4, 1, 4, 16, 8),
-    LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 1),
-    LB_VARIANT(3, KIND_BNN, 8, 2, 4, 8, 1),
-    LB_VARIANT(4, KIND_BNN, 8, 4, 4, 8, 1),
-    LB_VARIANT(5, KIND_BNN, 16, 2, 4, 8, 1),
-    LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8, 1),
-    LB_VARIANT(0, KIND_BNN, 8, 1, 4, 8, 4),
-    LB_VARIANT(0, KIND_BNN, 2, 1, 4, 16, 8),
+    LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 4),
+    LB_VARIANT(3, KIND_BNN, 8, 2, 8, 8, 4),
+    LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8, 4),
+    LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 4),
+    LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8, 2),
+    LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
 };
 const GemmVariant kTnn[] = {
     LB_VARIANT(1, KIND_TNN, 4, 1, 4, 16, 4),
-    LB_VARIANT(2, KIND_TNN, 8, 1, 4, 8, 1),
-    LB_VARIANT(3, KIND_TNN, 8, 2, 4, 8, 1),
-    LB_VARIANT(4, KIND_TNN, 8, 4, 4, 4, 1),
-    LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4, 1),
-    LB_VARIANT(0, KIND_TNN, 12, 4, 4, 4, 1),
-    LB_VARIANT(0, KIND_TNN, 8, 1, 4, 8, 2),
-    LB_VARIANT(0, KIND_TNN, 2, 1, 4, 16, 4),
+    LB_VARIANT(2, KIND_TNN, 8, 1, 4, 8, 2),
+    LB_VARIANT(3, KIND_TNN, 8, 2, 4, 4, 2),
+    LB_VARIANT(4, KIND_TNN, 8, 4, 4, 4, 2),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 4, 4, 1),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 4, 2, 1),
+    LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4, 2),
 };
 const GemmVariant kTbn[] = {
     LB_VARIANT(1, KIND_TBN, 4, 1, 4, 16, 8),
-    LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 1),
-    LB_VARIANT(3, KIND_TBN, 8, 2, 4, 8, 1),
-    LB_VARIANT(4, KIND_TBN, 8, 4, 4, 4, 1),
-    LB_VARIANT(5, KIND_TBN, 8, 4, 8, 4, 1),
-    LB_VARIANT(0, KIND_TBN, 16, 4, 4, 4, 1),
-    LB_VARIANT(0, KIND_TBN, 8, 1, 4, 8, 4),
-    LB_VARIANT(0, KIND_TBN, 2, 1, 4, 16, 8),
+    LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 4),
+    LB_VARIANT(3, KIND_TBN, 8, 2, 8, 8, 4),
+    LB_VARIANT(0, KIND_TBN, 8, 4, 8, 4, 1),
+    LB_VARIANT(0, KIND_TBN, 8, 4, 4, 4, 4),
+    LB_VARIANT(0, KIND_TBN, 8, 2, 4, 8, 4),
 };
 
 }  // namespace
