@@ -133,6 +133,8 @@ LB_API int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const u
  * gemm_i8_mfma -- the same product C = A B from UNPACKED int8 operands with int32 accumulation on the
  * integer matrix cores.  It plays the role the 8-bit gemmlowp multiplication (U8, Section IV, Table II/III)
  * plays in the paper: the comparison point for the low-bit kernels.  Any int8 values are allowed.
+ * Right operands of at most 16 columns (with M >= 64) are served by a streaming kernel built on packed 4 x int8 dot
+ * products instead of the matrix cores, which such a shape cannot fill.
  *   A  device, int8 row-major M x K, leading dimension lda >= K
  *   B  device, int8 row-major K x N, leading dimension ldb >= N
  *   C  device, int32 row-major M x N, leading dimension ldc >= N; overwritten.

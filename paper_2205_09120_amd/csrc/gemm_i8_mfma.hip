@@ -295,6 +295,9 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     // the 256 x 256 tile needs enough tiles to fill the 256 compute units; smaller problems use 128 x 128
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     int t = g_i8_forced;
+    // a right operand of at most 16 columns would leave a matrix-core tile almost empty: stream A with dot products
+    if (t < 0 && N <= 16 && M >= 64)
+        return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
     if (t < 0)
         t = big_tiles >= 512 ? 2 : 0;
     if (t == 1)

@@ -224,7 +224,8 @@ def test_deterministic():
 # ------------------------------------------------------------------------------------------------ int8 matrix-core comparator
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (128, 128, 64), (257, 300, 1000),
-                                   (512, 784, 2304), (33, 8, 4096), (300, 515, 131), (256, 256, 64)])
+                                   (512, 784, 2304), (33, 8, 4096), (300, 515, 131), (256, 256, 64),
+                                   (4096, 8, 2048), (100, 5, 3000), (64, 16, 4100), (257, 9, 16), (1000, 8, 8192)])
 def test_i8_mfma(M, N, K):
     say(f"gemm_i8_mfma M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
