@@ -279,6 +279,11 @@ def main() -> int:
         ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
         extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
         extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
+        # the same comparator with unsigned operands and zero points (eq. (3) corrections in the epilogue)
+        uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)      # {-1,0,1} -> {0,1,2}, zero point 1
+        tu8 = dev_time(lambda: lb.gemm_u8_mfma(M, N, K, uA, K, uB, N, 1, 1, C, N), 20)
+        extra["u8_zero_point_mfma_tops"] = w.ops / tu8 / 1e12
+        del uA, uB
         # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
         try:
             torch._int_mm(dA, dB)

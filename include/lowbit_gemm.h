@@ -143,6 +143,18 @@ LB_API int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_
                  int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * gemm_u8_mfma -- 8-bit linear-quantized product with zero points, the scheme of the paper's U8 baseline (eq. (2)
+ * and (3), as in gemmlowp):  C[i][j] = sum_t (A[i][t] - zA) * (B[t][j] - zB)  with unsigned 8-bit A, B and integer
+ * zero points 0 <= zA, zB <= 255, accumulated in int32.  Computed as eq. (3) prescribes: one matrix product on the
+ * matrix cores plus row-sum, column-sum and constant corrections.
+ *   A  device, uint8 row-major M x K, lda >= K;  B  device, uint8 row-major K x N, ldb >= N
+ *   C  device, int32 row-major M x N, ldc >= N; overwritten.
+ *   K <= 33025 so that |C| <= K * 255^2 fits int32 (the paper's eq. (4) bound for unsigned 32-bit is 66051).
+ */
+LB_API int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+                        int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream);
+
+/*
  * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
  *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
  *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel,

@@ -67,3 +67,21 @@ void oracle_gemm_i8_i32_samples(int64_t N, int64_t K, const int8_t *A, const int
         out[s] = acc;
     }
 }
+
+/* 8-bit linear-quantized product with zero points, the left-hand side of eq. (3) of the paper written out:
+ *     C[i][j] = sum_t (A[i][t] - zA) * (B[t][j] - zB)        A, B unsigned 8-bit, int32 accumulation. */
+void oracle_gemm_u8_zp_i32(int64_t M, int64_t N, int64_t K, const uint8_t *A, const uint8_t *B, int32_t zA,
+                           int32_t zB, int32_t *C)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        int32_t *c = C + i * N;
+        memset(c, 0, (size_t)N * sizeof(int32_t));
+        for (int64_t t = 0; t < K; ++t) {
+            const int32_t a = (int32_t)A[i * K + t] - zA;
+            const uint8_t *b = B + t * N;
+            for (int64_t j = 0; j < N; ++j)
+                c[j] += a * ((int32_t)b[j] - zB);
+        }
+    }
+}

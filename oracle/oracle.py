@@ -36,6 +36,8 @@ def _load() -> ctypes.CDLL:
         lib.oracle_gemm_i8_i32.restype = ctypes.c_int
         lib.oracle_gemm_i8_i32_samples.argtypes = [i64, i64, p, p, i64, p, p, p]
         lib.oracle_gemm_i8_i32_samples.restype = None
+        lib.oracle_gemm_u8_zp_i32.argtypes = [i64, i64, i64, p, p, ctypes.c_int32, ctypes.c_int32, p]
+        lib.oracle_gemm_u8_zp_i32.restype = None
         _lib = lib
     return _lib
 
@@ -80,3 +82,17 @@ def gemm_samples(A: np.ndarray, B: np.ndarray, ii: np.ndarray, jj: np.ndarray) -
     _load().oracle_gemm_i8_i32_samples(N, K, A.ctypes.data, B.ctypes.data, len(ii), ii.ctypes.data, jj.ctypes.data,
                                        out.ctypes.data)
     return out
+
+
+def gemm_u8_zero_point(A: np.ndarray, B: np.ndarray, zA: int, zB: int) -> np.ndarray:
+    """C[i][j] = sum_t (A[i][t] - zA)(B[t][j] - zB) for uint8 matrices (eq. (2)/(3) of the paper, left-hand side)."""
+    if A.dtype != np.uint8 or B.dtype != np.uint8:
+        raise TypeError("uint8 matrices expected")
+    if A.ndim != 2 or B.ndim != 2 or A.shape[1] != B.shape[0] or not (A.flags.c_contiguous and B.flags.c_contiguous):
+        raise ValueError("shape / layout mismatch")
+    M, K = A.shape
+    N = B.shape[1]
+    C = np.empty((M, N), dtype=np.int32)
+    if M and N:
+        _load().oracle_gemm_u8_zp_i32(M, N, K, A.ctypes.data, B.ctypes.data, int(zA), int(zB), C.ctypes.data)
+    return C

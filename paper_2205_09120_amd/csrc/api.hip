@@ -258,6 +258,40 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
     return LB_OK;
 }
 
+int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+                 int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream)
+{
+    const char *name = "gemm_u8_mfma";
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    if (zA < 0 || zA > 255 || zB < 0 || zB > 255)
+        return fail(LB_EINVAL, "%s: zero points zA=%d zB=%d must lie in [0, 255]", name, zA, zB);
+    // |(a - zA)(b - zB)| <= 255^2, so the int32 sum is safe up to K = floor((2^31 - 1) / 255^2)
+    if (K > 33025)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 33025 (int32 accumulation of 8-bit products)", name,
+                    (long long)K);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!A || !B || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (lda < K || ldb < N || ldc < N)
+        return fail(LB_EINVAL, "%s: lda=%lld ldb=%lld ldc=%lld too small", name, (long long)lda, (long long)ldb,
+                    (long long)ldc);
+    if (lda > INT64_MAX / M || ldb > INT64_MAX / K || ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
+    if (!aligned(C, 4))
+        return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    const hipError_t e =
+        lowbit::launch_gemm_u8(M, N, K, A, lda, B, ldb, zA, zB, C, ldc, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
 int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int64_t W, int64_t C, int kh, int kw,
                   int stride_h, int stride_w, int pad_h, int pad_w, uint64_t *Bp, void *stream)
 {

@@ -19,6 +19,12 @@
 // written to the other buffer afterwards, one barrier per step.  Measured on 1024 x 50176 x 4608 the 256 x 128
 // tile is the fastest of the three instances; the kernel is bound by the latency of the per-step global loads
 // (one step of prefetch, one wave per SIMD), not by the matrix cores.
+//
+// Unsigned 8-bit operands with zero points (U8 = true; eq. (2) and (3) of the paper, the gemmlowp scheme): the
+// bytes are re-biased to signed on the way in (x' = x - 128, one XOR), the matrix cores form sum a'b', and the
+// epilogue applies  C = sum a'b' - zB' * rowsum(a') - zA' * colsum(b') + K * zA' * zB'  with zA' = zA - 128,
+// zB' = zB - 128, which equals sum (a - zA)(b - zB).  Row and column sums are accumulated with packed dot products
+// by the threads that stage the tiles, and combined through LDS after the depth loop.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -46,12 +52,17 @@ __device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t o[4])
     o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-template <int TM, int TN, int MODE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_mfma_kernel(int M, int N, int K, const int8_t *__restrict__ A,
-                                                           int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
-                                                           int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB,
-                                                           int tiles_per_xcd)
+__device__ __forceinline__ int32_t bytesum(uint32_t x, int32_t c)
 {
+    return __builtin_amdgcn_sdot4((int)x, 0x01010101, c, false);
+}
+
+template <int TM, int TN, int MODE, bool U8>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_mfma_kernel(
+    int M, int N, int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
+    int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
+{
+    constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;  // unsigned byte -> signed byte minus 128
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int NQ = BN / 4;                       // column quads per tile
     constexpr int B_PLANE = NQ * 16 + 32;            // bytes per (depth block, column%4) plane
@@ -91,7 +102,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)(m0 + (u >> 2)) * lda + k0 + (u & 3) * 16);
             // four dwords assembled by value (the compiler merges them into one 128-bit load); copying the uint4
             // as an aggregate makes the optimiser keep a_pre in memory and demote it to LDS
-            a_pre[p] = make_uint4(src[0], src[1], src[2], src[3]);
+            a_pre[p] = make_uint4(src[0] ^ FLIP, src[1] ^ FLIP, src[2] ^ FLIP, src[3] ^ FLIP);
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -100,7 +111,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const int8_t *src = B + (int64_t)(k0 + kb * 16) * ldb + n0 + nq * 4;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                b_pre[p][j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb);
+                b_pre[p][j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb) ^ FLIP;
         }
     };
     auto fetch_clamped = [&](int k0) __attribute__((always_inline)) {
@@ -111,7 +122,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const bool ok = r < M && k + 16 <= K;
             const int rr = r < M ? r : M - 1, kk = k + 16 <= K ? k : K - 16;
             const uint4 v = *reinterpret_cast<const uint4 *>(A + (int64_t)rr * lda + kk);
-            a_pre[p] = ok ? v : make_uint4(0u, 0u, 0u, 0u);
+            a_pre[p] = ok ? make_uint4(v.x ^ FLIP, v.y ^ FLIP, v.z ^ FLIP, v.w ^ FLIP) : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -124,7 +135,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 const int k = k0 + kb * 16 + j;
                 const int kk = k < K ? k : K - 1;
                 const uint32_t x = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
-                b_pre[p][j] = (k < K && n + 4 <= N) ? x : 0u;
+                b_pre[p][j] = (k < K && n + 4 <= N) ? (x ^ FLIP) : 0u;
             }
         }
     };
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             uint32_t w[4] = {0u, 0u, 0u, 0u};
             if (r < M)
                 for (int i = 0; i < 16 && k + i < K; ++i)
-                    w[i >> 2] |= (uint32_t)(uint8_t)A[(int64_t)r * lda + k + i] << (8 * (i & 3));
+                    w[i >> 2] |= (uint32_t)((uint8_t)A[(int64_t)r * lda + k + i] ^ (FLIP & 0xffu)) << (8 * (i & 3));
             a_pre[p] = make_uint4(w[0], w[1], w[2], w[3]);
         }
 #pragma unroll
@@ -149,7 +160,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 uint32_t x = 0u;
                 if (k < K)
                     for (int i = 0; i < 4 && n + i < N; ++i)
-                        x |= (uint32_t)(uint8_t)B[(int64_t)k * ldb + n + i] << (8 * i);
+                        x |= (uint32_t)((uint8_t)B[(int64_t)k * ldb + n + i] ^ (FLIP & 0xffu)) << (8 * i);
                 b_pre[p][j] = x;
             }
         }
@@ -162,12 +173,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         else
             fetch_bytes(k0);
     };
+    // U8: signed sums of the staged bytes, per thread; the rows / columns a thread stages are the same in every step
+    int32_t rs_acc[A_PT], cs_acc[B_PT][4];
+#pragma unroll
+    for (int p = 0; p < A_PT; ++p)
+        rs_acc[p] = 0;
+#pragma unroll
+    for (int p = 0; p < B_PT; ++p)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            cs_acc[p][i] = 0;
+
     auto commit = [&](int buf) __attribute__((always_inline)) {
         uint8_t *As = smem[buf], *Bs = smem[buf] + A_BYTES;
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
             *reinterpret_cast<uint4 *>(&As[(u >> 2) * A_STRIDE + (u & 3) * 16]) = a_pre[p];
+            if constexpr (U8)
+                rs_acc[p] = bytesum(a_pre[p].x, bytesum(a_pre[p].y, bytesum(a_pre[p].z, bytesum(a_pre[p].w, rs_acc[p]))));
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -180,9 +204,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             for (int q = 0; q < 4; ++q)
                 transpose4x4(&b_pre[p][q * 4], o[q]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
                 *reinterpret_cast<uint4 *>(&Bs[kb * B_BLOCK + i * B_PLANE + nq * 16]) =
                     make_uint4(o[0][i], o[1][i], o[2][i], o[3][i]);
+                if constexpr (U8)
+                    cs_acc[p][i] = bytesum(o[0][i], bytesum(o[1][i], bytesum(o[2][i], bytesum(o[3][i], cs_acc[p][i]))));
+            }
         }
     };
 
@@ -228,15 +255,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     for (int s = 0; s < nsteps; ++s) {
         if (s + 1 < nsteps)
             fetch((s + 1) * BK);
-        // keep the instruction scheduler from hoisting the LDS stores of the next step (and with them the wait
-        // for the loads just issued) above the multiplication
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
         compute(s & 1);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("" ::: "memory");
         if (s + 1 < nsteps)
             commit((s + 1) & 1);
+        __syncthreads();
+    }
+
+    // U8: combine the per-thread sums through LDS (the tile buffers are free after the last barrier):
+    // rsum[row][4 depth quarters], csum[column][4 depth blocks]
+    int32_t *rsum = reinterpret_cast<int32_t *>(&smem[0][0]);
+    int32_t *csum = rsum + BM * 4;
+    if constexpr (U8) {
+        static_assert((BM + BN) * 4 * 4 <= 2 * (A_BYTES + B_BYTES), "sums must fit the tile buffers");
+#pragma unroll
+        for (int p = 0; p < A_PT; ++p)
+            rsum[tid + p * 256] = rs_acc[p];                      // unit u = row*4 + quarter
+#pragma unroll
+        for (int p = 0; p < B_PT; ++p) {
+            const int u = tid + p * 256;
+            if (B_UNITS % 256 != 0 && u >= B_UNITS)
+                continue;
+            const int kb = u / NQ, nq = u % NQ;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                csum[(nq * 4 + i) * 4 + kb] = cs_acc[p][i];
+        }
         __syncthreads();
     }
 
@@ -245,19 +288,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+            const int lcol = (wn * TN + j) * 32 + (lane & 31);
+            const int col = n0 + lcol;
+            int32_t ccorr = 0;
+            if constexpr (U8)
+                ccorr = K * zA * zB - zA * (csum[lcol * 4] + csum[lcol * 4 + 1] + csum[lcol * 4 + 2] + csum[lcol * 4 + 3]);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int lrow = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int row = m0 + lrow;
+                int32_t out = acc[i][j][r];
+                if constexpr (U8)
+                    out += ccorr - zB * (rsum[lrow * 4] + rsum[lrow * 4 + 1] + rsum[lrow * 4 + 2] + rsum[lrow * 4 + 3]);
                 if (row < M && col < N)
-                    C[(int64_t)row * ldc + col] = acc[i][j][r];
+                    C[(int64_t)row * ldc + col] = out;
             }
         }
 }
 
-template <int TM, int TN>
+template <int TM, int TN, bool U8>
 hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
-                       int32_t *C, int64_t ldc, hipStream_t stream)
+                       int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const int nMB = (int)((M + BM - 1) / BM), nNB = (int)((N + BN - 1) / BN);
@@ -272,14 +323,14 @@ hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t
     const bool can_clamp = (N % 4) == 0 && (K % 16) == 0 && N >= 4 && K >= 16;
     const dim3 g((unsigned)grid), b(256);
     if (aligned && whole)
-        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 0>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B, ldb,
-                           C, ldc, nMB, nNB, tiles_per_xcd);
+        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 0, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
+                           ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     else if (aligned && can_clamp)
-        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 1>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B, ldb,
-                           C, ldc, nMB, nNB, tiles_per_xcd);
+        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 1, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
+                           ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     else
-        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 2>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B, ldb,
-                           C, ldc, nMB, nNB, tiles_per_xcd);
+        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 2, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
+                           ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     return hipGetLastError();
 }
 
@@ -292,7 +343,7 @@ void i8_force_tile(int t) { g_i8_forced = t; }
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    // the 256 x 256 tile needs enough tiles to fill the 256 compute units; smaller problems use 128 x 128
+    // the 256 x 128 tile needs enough tiles to fill the 256 compute units; smaller problems use 128 x 128
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     int t = g_i8_forced;
     // a right operand of at most 16 columns would leave a matrix-core tile almost empty: stream A with dot products
@@ -301,10 +352,21 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     if (t < 0)
         t = big_tiles >= 512 ? 2 : 0;
     if (t == 1)
-        return launch_tile<4, 4>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+        return launch_tile<4, 4, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     if (t == 2)
-        return launch_tile<4, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream);
-    return launch_tile<2, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+        return launch_tile<4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+    return launch_tile<2, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+}
+
+// unsigned operands with zero points; zA, zB in [0, 255]
+hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+                          int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
+{
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    const int8_t *a = reinterpret_cast<const int8_t *>(A), *b = reinterpret_cast<const int8_t *>(B);
+    if (big_tiles >= 512)
+        return launch_tile<4, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+    return launch_tile<2, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
 }
 
 }  // namespace lowbit

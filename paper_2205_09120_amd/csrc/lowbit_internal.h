@@ -60,6 +60,8 @@ hipError_t launch_im2col_packed(int planes, const uint64_t *Fp, uint64_t *Bp, co
 // int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream);
+hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+                          int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream);
 hipError_t launch_gemm_i8_skinny(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
                                  int64_t ldb, int32_t *C, int64_t ldc, hipStream_t stream);
 void i8_force_tile(int t);  // -1 = shape-based, 0 = 128x128, 1 = 256x256, 2 = 256x128

@@ -98,6 +98,16 @@ def test_im2col_argument_validation(L):
     assert f(fake, 2, 1, 1 << 25, 8, 64, 3, 3, 1, 1, 1, 1, fake, None) == binding.LB_EOVERFLOW
 
 
+def test_u8_argument_validation(L):
+    fake = 0x1000
+    f = L.gemm_u8_mfma
+    assert f(4, 4, 16, fake, 16, fake, 4, 256, 0, fake, 4, None) == binding.LB_EINVAL      # zero point out of range
+    assert f(4, 4, 16, fake, 16, fake, 4, 0, -1, fake, 4, None) == binding.LB_EINVAL
+    assert f(4, 4, 33026, fake, 33026, fake, 4, 0, 0, fake, 4, None) == binding.LB_EOVERFLOW
+    assert f(4, 4, 16, fake, 8, fake, 4, 0, 0, fake, 4, None) == binding.LB_EINVAL         # lda < K
+    assert f(0, 4, 16, None, 16, None, 4, 0, 0, None, 4, None) == binding.LB_OK
+
+
 def test_variant_hooks(L):
     for op in range(3):
         n = L.lb_num_variants(op)

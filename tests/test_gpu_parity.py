@@ -307,3 +307,31 @@ def test_sparse_and_dense_ternary_extremes():
         assert np.array_equal(run_gemm("tbn", A, B).cpu().numpy(), oracle.gemm(A, B))
     A, B = synth.make_custom("tbn", 70, 90, 300, seed=3)
     assert not run_gemm("tbn", np.zeros_like(A), B).cpu().numpy().any()
+
+
+# ------------------------------------------------------------------------------------------------ U8 with zero points (eq. (3))
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (257, 300, 1000), (512, 784, 2304),
+                                   (33, 8, 4096), (300, 515, 131), (1024, 2048, 320)])
+def test_u8_zero_point_gemm(M, N, K):
+    rng = np.random.default_rng(M * 3 + N * 5 + K)
+    A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
+    B = rng.integers(0, 256, size=(K, N), dtype=np.uint8)
+    for zA, zB in ((0, 0), (128, 128), (17, 240)):
+        say(f"gemm_u8_mfma M={M} N={N} K={K} zA={zA} zB={zB}")
+        got = lb.gemm_u8_mfma(M, N, K, dev(A), K, dev(B), N, zA, zB)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), oracle.gemm_u8_zero_point(A, B, zA, zB)), (zA, zB)
+
+
+def test_u8_extreme_values_and_depth_limit():
+    say("gemm_u8_mfma extremes")
+    K = 33025
+    A = np.full((70, K), 255, dtype=np.uint8)
+    B = np.zeros((K, 66), dtype=np.uint8)
+    got = lb.gemm_u8_mfma(70, 66, K, dev(A), K, dev(B), 66, 0, 255)
+    torch.cuda.synchronize()
+    assert np.all(got.cpu().numpy() == -K * 255 * 255)
+    with pytest.raises(lb.LowbitError) as e:
+        lb.gemm_u8_mfma(70, 66, K + 1, dev(A), K + 1, dev(B), 66, 0, 255)
+    assert e.value.status == lb.LB_EOVERFLOW

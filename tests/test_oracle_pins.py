@@ -299,3 +299,29 @@ def test_generator_statistics():
     wb = synth.WORKLOADS["cfg2_bnn_conv3x3x128_56x56"]
     Ab, _ = synth.make_inputs(wb)
     assert set(np.unique(Ab)) == {-1, 1} and abs((Ab == 1).mean() - 0.5) < 0.01
+
+
+# ---------------------------------------------------------------- zero-point product (eq. (2), (3))
+
+@pytest.mark.parametrize("zA,zB", [(0, 0), (128, 128), (3, 250), (255, 1)])
+def test_zero_point_oracle_against_eq3_expansion(zA, zB):
+    """The oracle evaluates the left-hand side of eq. (3); the right-hand side (product of the quantized matrices
+    minus row-sum, column-sum terms plus k*zA*zB), evaluated with a library matmul, must agree."""
+    rng = np.random.default_rng(zA * 256 + zB)
+    A = rng.integers(0, 256, size=(23, 301), dtype=np.uint8)
+    B = rng.integers(0, 256, size=(301, 17), dtype=np.uint8)
+    a, b = A.astype(np.int64), B.astype(np.int64)
+    rhs = a @ b - zB * a.sum(axis=1, keepdims=True) - zA * b.sum(axis=0, keepdims=True) + 301 * zA * zB
+    assert np.array_equal(oracle.gemm_u8_zero_point(A, B, zA, zB), rhs)
+
+
+def test_zero_point_special_cases():
+    A = np.full((3, 10), 7, dtype=np.uint8)
+    B = np.full((10, 4), 9, dtype=np.uint8)
+    assert np.all(oracle.gemm_u8_zero_point(A, B, 7, 200) == 0)                 # A equals its zero point everywhere
+    assert np.all(oracle.gemm_u8_zero_point(A, B, 5, 6) == 10 * 2 * 3)
+    assert np.all(oracle.gemm_u8_zero_point(A, B, 0, 0) == 10 * 63)
+    # extreme magnitudes: 255^2 per term
+    A = np.full((1, 100), 255, dtype=np.uint8)
+    B = np.zeros((100, 1), dtype=np.uint8)
+    assert oracle.gemm_u8_zero_point(A, B, 0, 255)[0, 0] == -100 * 255 * 255
