@@ -279,6 +279,14 @@ def main() -> int:
         ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
         extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
         extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
+        # product with the activation threshold fused into the epilogue (packed ternary output instead of int32 C)
+        qlo = torch.full((M,), -20, dtype=torch.int32, device="cuda")
+        qhi = torch.full((M,), 20, dtype=torch.int32, device="cuda")
+        qout = torch.empty(lb.packed_ternary_bytes(N, M) // 8, dtype=torch.int64, device="cuda")
+        trq = dev_time(lambda: lb.gemm_requant("tnn", 2, M, N, K, Ap, Bp, qlo, qhi, qout), 20)
+        extra["gemm_requant_ternary_ms"] = trq * 1e3
+        extra["gemm_requant_ternary_tops"] = w.ops / trq / 1e12
+        del qout
         # the same comparator with unsigned operands and zero points (eq. (3) corrections in the epilogue)
         uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)      # {-1,0,1} -> {0,1,2}, zero point 1
         tu8 = dev_time(lambda: lb.gemm_u8_mfma(M, N, K, uA, K, uB, N, 1, 1, C, N), 20)

@@ -130,6 +130,23 @@ LB_API int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const u
              void *stream);
 
 /*
+ * gemm_requant -- gemm_bnn / gemm_tnn / gemm_tbn with the activation threshold fused into the epilogue: instead of
+ * the int32 matrix C the call writes the low-bit feature map the next layer consumes, already packed.  The paper's
+ * algorithms stop at the integer C (Section III); this is the step that follows it in a BNN / TNN / TBN layer.
+ *
+ *   kind        0 = BNN, 1 = TNN, 2 = TBN operands (Ap, Bp as for the corresponding gemm_* call)
+ *   out_planes  2: ternary output  y = -1 if c < lo[i], +1 if c > hi[i] (and not c < lo[i]), else 0
+ *               1: binary output   y = -1 if c < lo[i], else +1   (hi is not read and may be NULL)
+ *   lo, hi      device, int32[M]: thresholds per row i of C (per filter / output channel)
+ *   Out         device, N bit strings of depth M in the packed format (string j = column j of C, i.e. one output
+ *               pixel; depth position i = output channel): packed_binary_bytes(N, M) or packed_ternary_bytes(N, M)
+ *               bytes, overwritten completely (pad bits zero).  This is the layout pack_* produces for an NHWC
+ *               feature map with M channels, ready for im2col_packed or as the B operand of the next product.
+ */
+LB_API int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t K, const uint64_t *Ap,
+                        const uint64_t *Bp, const int32_t *lo, const int32_t *hi, uint64_t *Out, void *stream);
+
+/*
  * gemm_i8_mfma -- the same product C = A B from UNPACKED int8 operands with int32 accumulation on the
  * integer matrix cores.  It plays the role the 8-bit gemmlowp multiplication (U8, Section IV, Table II/III)
  * plays in the paper: the comparison point for the low-bit kernels.  Any int8 values are allowed.

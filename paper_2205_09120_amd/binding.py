@@ -20,7 +20,7 @@ OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
 _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
-           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
+           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name")
 
 
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
         L.gemm_i8_mfma.restype = ci
         L.gemm_i8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.gemm_requant.restype = ci
+        L.gemm_requant.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.gemm_u8_mfma.restype = ci
         L.gemm_u8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, ctypes.c_int32, ctypes.c_int32, vp, i64, vp]
         L.lb_set_variant.restype = ci
@@ -165,6 +167,16 @@ def gemm_i8_mfma(M, N, K, A, lda, B, ldb, C=None, ldc=None, stream=None):
         ldc = C.stride(0)
     _check(lib().gemm_i8_mfma(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, _stream(stream)))
     return C
+
+
+def gemm_requant(kind, out_planes: int, M, N, K, Ap, Bp, lo, hi=None, Out=None, stream=None):
+    """Thresholded product written as N packed strings of depth M (1 = binary, 2 = ternary planes)."""
+    if Out is None:
+        nbytes = packed_ternary_bytes(N, M) if out_planes == 2 else packed_binary_bytes(N, M)
+        Out = torch.empty(nbytes // 8, dtype=torch.int64, device=Ap.device)
+    _check(lib().gemm_requant(_OPS.get(kind, kind), out_planes, M, N, K, _ptr(Ap), _ptr(Bp), _ptr(lo), _ptr(hi),
+                              _ptr(Out), _stream(stream)))
+    return Out
 
 
 def gemm_u8_mfma(M, N, K, A, lda, B, ldb, zA: int, zB: int, C=None, ldc=None, stream=None):

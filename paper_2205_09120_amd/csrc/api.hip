@@ -258,6 +258,55 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
     return LB_OK;
 }
 
+int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
+                 const int32_t *lo, const int32_t *hi, uint64_t *Out, void *stream)
+{
+    const char *name = "gemm_requant";
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    if (out_planes != 1 && out_planes != 2)
+        return fail(LB_EINVAL, "%s: out_planes=%d must be 1 (binary) or 2 (ternary)", name, out_planes);
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    if (K > kMaxDepth || M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld K=%lld exceed 2^31-1", name, (long long)M, (long long)N,
+                    (long long)K);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!Ap || !Bp || !Out || !lo || (out_planes == 2 && !hi))
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(Out, 16) || !aligned(lo, 4) || !aligned(hi, 4))
+        return fail(LB_EINVAL, "%s: packed operands must be 16-byte aligned, thresholds 4-byte aligned", name);
+    if (packed_bytes(N, M, out_planes == 2 ? 16 : 8) == 0)
+        return fail(LB_EOVERFLOW, "%s: output size overflows", name);
+    const int64_t KW = (K + 63) / 64;
+    int count = 0;
+    const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
+    // lanes own rows of C (output channels): a wave-wide vote then yields one packed depth word of the output
+    lowbit::GemmArgs a;
+    a.Sp = reinterpret_cast<const uint32_t *>(Bp);
+    a.rowsS = (int)N;
+    a.Vp = reinterpret_cast<const uint32_t *>(Ap);
+    a.rowsV = (int)M;
+    a.KW = (int)KW;
+    a.K = (int)K;
+    a.C = nullptr;
+    a.ldc = 0;
+    a.stream = static_cast<hipStream_t>(stream);
+    a.q_lo = lo;
+    a.q_hi = hi;
+    a.q_out = Out;
+    a.q_planes = out_planes;
+    const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
+    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV);
+    const hipError_t e = tab[v].launch_transposed(a);
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
 int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
                  int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream)
 {

@@ -85,7 +85,10 @@ template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
 __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
                                                                const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
                                                                int KW, int K, int32_t *__restrict__ C, int64_t ldc,
-                                                               int nSB, int nVB, int tiles_per_xcd)
+                                                               int nSB, int nVB, int tiles_per_xcd,
+                                                               const int32_t *__restrict__ q_lo,
+                                                               const int32_t *__restrict__ q_hi,
+                                                               uint64_t *__restrict__ q_out, int q_planes)
 {
     using T = Traits<KIND>;
     constexpr int SD = T::SD, VD = T::VD;
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         __syncthreads();
     }
 
-    // epilogue: eq. (6) / (7), int32 store
+    // epilogue: eq. (6) / (7), then either the int32 store or (transposed orientation only) re-quantization
 #pragma unroll
     for (int t = 0; t < TV; ++t) {
         const int v = v0 + t * 64 + lane;
@@ -304,6 +307,30 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                 out[i] = acc[0][i][t] - 2 * acc[1][i][t];
             else
                 out[i] = nnz[t] - 2 * acc[0][i][t];
+        }
+        if constexpr (TR) {
+            if (q_out != nullptr) {
+                // Lanes own 64 consecutive V rows (channels), so a wave-wide vote on "c > hi" / "c < lo" is exactly one
+                // 64-bit depth word of the packed output string of S row s0+i.  Lane 0 stores it.
+                const bool live = v < rowsV;
+                const int32_t lo = live ? q_lo[v] : 0, hi = (live && q_planes == 2) ? q_hi[v] : 0;
+                const int64_t mw = ((int64_t)rowsV + 63) / 64;
+#pragma unroll
+                for (int i = 0; i < TS; ++i) {
+                    const uint64_t minus = __ballot(live && out[i] < lo);
+                    const uint64_t plus = __ballot(live && out[i] > hi && !(out[i] < lo));
+                    if (lane == 0 && s0 + i < rowsS && (v0 >> 6) + t < mw) {
+                        const int64_t word = (int64_t)(s0 + i) * mw + (v0 >> 6) + t;
+                        if (q_planes == 2) {
+                            q_out[word * 2] = plus;
+                            q_out[word * 2 + 1] = minus;
+                        } else {
+                            q_out[word] = minus;
+                        }
+                    }
+                }
+                continue;
+            }
         }
         if (v < rowsV) {
             if constexpr (!TR) {
@@ -341,7 +368,8 @@ hipError_t launch(const GemmArgs &a)
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, SG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
-                       a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd);
+                       a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd, a.q_lo,
+                       a.q_hi, a.q_out, a.q_planes);
     return hipGetLastError();
 }
 

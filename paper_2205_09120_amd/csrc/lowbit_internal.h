@@ -18,6 +18,13 @@ struct GemmArgs {
     int32_t *C;
     int64_t ldc;
     hipStream_t stream;
+    // Re-quantized output (transposed launcher only; q_out == nullptr selects the int32 store): instead of C, one
+    // packed bit string per S row is written whose depth runs over the V rows, q_planes = 1 binary / 2 ternary,
+    // thresholds per V row.
+    const int32_t *q_lo = nullptr;
+    const int32_t *q_hi = nullptr;
+    uint64_t *q_out = nullptr;
+    int q_planes = 0;
 };
 
 struct GemmVariant {

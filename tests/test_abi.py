@@ -108,6 +108,17 @@ def test_u8_argument_validation(L):
     assert f(0, 4, 16, None, 16, None, 4, 0, 0, None, 4, None) == binding.LB_OK
 
 
+def test_requant_argument_validation(L):
+    fake = 0x1000
+    f = L.gemm_requant
+    assert f(3, 2, 4, 4, 64, fake, fake, fake, fake, fake, None) == binding.LB_EINVAL        # kind
+    assert f(1, 3, 4, 4, 64, fake, fake, fake, fake, fake, None) == binding.LB_EINVAL        # planes
+    assert f(1, 2, 4, 4, 0, fake, fake, fake, fake, fake, None) == binding.LB_EINVAL         # K
+    assert f(1, 2, 4, 4, 64, fake, fake, fake, None, fake, None) == binding.LB_EINVAL        # ternary needs hi
+    assert f(1, 2, 4, 4, 64, fake, fake, fake, fake, fake + 8, None) == binding.LB_EINVAL    # Out misaligned
+    assert f(0, 1, 0, 4, 64, None, None, None, None, None, None) == binding.LB_OK
+
+
 def test_variant_hooks(L):
     for op in range(3):
         n = L.lb_num_variants(op)

@@ -325,3 +325,25 @@ def test_zero_point_special_cases():
     A = np.full((1, 100), 255, dtype=np.uint8)
     B = np.zeros((100, 1), dtype=np.uint8)
     assert oracle.gemm_u8_zero_point(A, B, 0, 255)[0, 0] == -100 * 255 * 255
+
+
+# ---------------------------------------------------------------- activation thresholds
+
+def test_requantize_definition():
+    from oracle import requant
+    C = np.array([[-5, -1, 0, 1, 5], [10, 11, 12, 13, 14]], dtype=np.int32)
+    lo, hi = np.array([-1, 12], dtype=np.int32), np.array([1, 12], dtype=np.int32)
+    Yt = requant.requantize(C, lo, hi, True)
+    assert Yt.shape == (5, 2)
+    assert Yt[:, 0].tolist() == [-1, 0, 0, 0, 1] and Yt[:, 1].tolist() == [-1, -1, 0, 1, 1]
+    Yb = requant.requantize(C, lo, None, False)
+    assert Yb[:, 0].tolist() == [-1, 1, 1, 1, 1] and Yb[:, 1].tolist() == [-1, -1, 1, 1, 1]
+    # vectorised restatement on random data
+    rng = np.random.default_rng(0)
+    C = rng.integers(-50, 50, size=(7, 9)).astype(np.int32)
+    lo = rng.integers(-20, 0, size=7).astype(np.int32)
+    hi = rng.integers(0, 20, size=7).astype(np.int32)
+    want = np.where(C < lo[:, None], -1, np.where(C > hi[:, None], 1, 0)).T
+    assert np.array_equal(requant.requantize(C, lo, hi, True), want)
+    # crossed thresholds never give the invalid code: the minus test wins
+    assert requant.requantize(np.array([[0]], dtype=np.int32), np.array([5]), np.array([-5]), True)[0, 0] == -1
