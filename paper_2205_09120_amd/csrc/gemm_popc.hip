@@ -1,6 +1,7 @@
 // Tiled popcount GEMM kernels for gfx950 (binary / ternary / ternary-binary, Section III of the paper).
 //
-// Design (differs from the paper's NEON microkernels on purpose; see the notes at the end of this comment):
+// Design (differs from the paper's NEON microkernels on purpose: those are built around 128-bit registers, 16-bit
+// accumulators and reordered operand blocks; here the wavefront, its scalar register file and LDS set the shape):
 //   * One operand ("S", the scalar side) is read with scalar loads straight into SGPRs: every lane of a
 //     wavefront works on the same TS bit strings of S, so they cost no vector registers and no LDS traffic.
 //   * The other operand ("V", the vector side) is staged through LDS once per workgroup and every lane owns
@@ -13,7 +14,9 @@
 //     where nz = x+ | x- and neg = x-.  With P = popcount(z+), Q = popcount(z-) of eq. (7): M = P + Q and U = Q,
 //     so C = M - 2U (TNN) and C = popcount(nz_v) - 2U (TBN) are the integers eq. (7) defines; the forms need
 //     fewer instructions than evaluating z+ and z- separately because gfx950 has a three-input bit operation.
-//   * Accumulators are 32-bit; the epilogue applies eq. (6) / (7) and writes int32 C.
+//   * Accumulators are 32-bit; the epilogue applies eq. (6) / (7) and writes int32 C, or, in the orientation where
+//     lanes own rows of C, compares against per-row thresholds and writes the packed low-bit feature map directly.
+//   * Workgroup ids are mapped to tiles XCD by XCD so that the workgroups sharing a V tile share an L2.
 //
 // The ternary planes are converted from the stored (x+, x-) pair to (nz, neg) while the tile is staged, so the
 // packed format in memory stays the paper's encoding.
@@ -74,9 +77,9 @@ __device__ __forceinline__ void popc_acc(int32_t &acc, uint32_t x)
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
 }
 
-// SG depth words of an S string fetched by one scalar load (SG*SD dwords, at most 16).  Large tiles use SG = 1;
-// the small, latency-bound tiles fetch up to 16 dwords per string at once so that a wave waits for scalar memory
-// once per SG depth words instead of once per word.
+// SG depth words of an S string are fetched by one scalar load (SG*SD dwords, at most 16), so that a wave waits for
+// scalar memory once per SG depth words instead of once per word: 2 or 4 words for the large tiles (bounded by the
+// SGPR budget of TS = 8 strings), up to 16 dwords for the small, latency-bound tile.
 template <int N> struct alignas(4) Words { uint32_t w[N]; };
 
 template <int N> using IntC = std::integral_constant<int, N>;
