@@ -117,45 +117,81 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
     const int64_t kbase = w * 64;
 
     uint32_t neg[8], pos[8];
+    // Workgroups whose 128 strings x 512 depth positions lie inside the matrix take straight-line loads (a load
+    // inside a divergent branch forces a wait right behind it); edge workgroups take the guarded path.
+    const bool interior = (rb + 1) * 128 <= rows && (wb + 1) * 512 <= K;
+    if (interior) {
+        const int8_t *p = src + kbase * stride_k + r0;
 #pragma unroll
-    for (int kb = 0; kb < 8; ++kb) {
-        uint32_t an = 0u, ap = 0u;
+        for (int kb = 0; kb < 8; ++kb) {
+            uint32_t x[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int64_t k = kbase + kb * 8 + j;
-            uint32_t x = 0u;
-            if (k < K && r0 < rows) {
-                const int8_t *p = src + k * stride_k + r0;
-                if (r0 + 4 <= rows) {
-                    x = *reinterpret_cast<const uint32_t *>(p);
-                } else {
-                    for (int i = 0; i < (int)(rows - r0); ++i)
-                        x |= (uint32_t)(uint8_t)p[i] << (8 * i);
-                }
+            for (int j = 0; j < 8; ++j) {
+                x[j] = *reinterpret_cast<const uint32_t *>(p);
+                p += stride_k;
             }
-            an = (an >> 1) | neg7(x);
-            if (TERNARY)
-                ap = (ap >> 1) | pos7(x);
+            uint32_t an = 0u, ap = 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                an = (an >> 1) | neg7(x[j]);
+                if (TERNARY)
+                    ap = (ap >> 1) | pos7(x[j]);
+            }
+            neg[kb] = an;
+            pos[kb] = ap;
         }
-        neg[kb] = an;  // byte i = 8 depth bits of string r0+i
-        pos[kb] = ap;
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < 8; ++kb) {
+            uint32_t an = 0u, ap = 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int64_t k = kbase + kb * 8 + j;
+                uint32_t x = 0u;
+                if (k < K && r0 < rows) {
+                    const int8_t *p = src + k * stride_k + r0;
+                    if (r0 + 4 <= rows) {
+                        x = *reinterpret_cast<const uint32_t *>(p);
+                    } else {
+                        for (int i = 0; i < (int)(rows - r0); ++i)
+                            x |= (uint32_t)(uint8_t)p[i] << (8 * i);
+                    }
+                }
+                an = (an >> 1) | neg7(x);
+                if (TERNARY)
+                    ap = (ap >> 1) | pos7(x);
+            }
+            neg[kb] = an;  // byte i = 8 depth bits of string r0+i
+            pos[kb] = ap;
+        }
     }
-    // byte transpose: string i gets bytes i of neg[0..3] (low dword) and neg[4..7] (high dword)
+    // byte transpose: string i gets bytes i of neg[0..3] (low dword) and of neg[4..7] (high dword)
+    auto transpose4 = [](const uint32_t *a, uint32_t *o) __attribute__((always_inline)) {
+        const uint32_t t0 = __builtin_amdgcn_perm(a[1], a[0], 0x05010400u), t1 = __builtin_amdgcn_perm(a[1], a[0], 0x07030602u);
+        const uint32_t t2 = __builtin_amdgcn_perm(a[3], a[2], 0x05010400u), t3 = __builtin_amdgcn_perm(a[3], a[2], 0x07030602u);
+        o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+        o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+        o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+        o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+    };
+    uint32_t nlo[4], nhi[4], plo[4], phi[4];
+    transpose4(neg, nlo);
+    transpose4(neg + 4, nhi);
+    if (TERNARY) {
+        transpose4(pos, plo);
+        transpose4(pos + 4, phi);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        auto col = [&](const uint32_t *a, int base) {
-            return ((a[base] >> (8 * i)) & 0xffu) | (((a[base + 1] >> (8 * i)) & 0xffu) << 8) |
-                   (((a[base + 2] >> (8 * i)) & 0xffu) << 16) | (((a[base + 3] >> (8 * i)) & 0xffu) << 24);
-        };
         uint32_t *e = &tile[quad * 4 + i][wl * ED];
         if (TERNARY) {
-            e[0] = col(pos, 0);
-            e[1] = col(pos, 4);
-            e[2] = col(neg, 0);
-            e[3] = col(neg, 4);
+            e[0] = plo[i];
+            e[1] = phi[i];
+            e[2] = nlo[i];
+            e[3] = nhi[i];
         } else {
-            e[0] = col(neg, 0);
-            e[1] = col(neg, 4);
+            e[0] = nlo[i];
+            e[1] = nhi[i];
         }
     }
     __syncthreads();
