@@ -271,6 +271,25 @@ def main() -> int:
         return a.elapsed_time(b) * 1e-3 / (replays * per_graph)
 
     if not args.no_extra:
+        # what the machine sustains for the two roofline bounds (calibration kernels of the library)
+        sink = torch.empty(lb.lb_calib_sink_bytes() // 4, dtype=torch.int32, device="cuda")
+        iters = 4096
+        tv = dev_time(lambda: lb.lb_calib_valu(1, iters, sink), 5)
+        valu_measured = lb.lb_calib_valu_lane_instr(iters) / tv / 1e12
+        tv0 = dev_time(lambda: lb.lb_calib_valu(0, iters, sink), 5)
+        big = 1 << 31
+        s_buf = torch.empty(big, dtype=torch.uint8, device="cuda").fill_(3)
+        d_buf = torch.empty(big, dtype=torch.uint8, device="cuda")
+        tr = dev_time(lambda: lb.lb_calib_stream(0, s_buf, None, big, sink), 5)
+        tw = dev_time(lambda: lb.lb_calib_stream(1, None, d_buf, big, sink), 5)
+        tc = dev_time(lambda: lb.lb_calib_stream(2, s_buf, d_buf, big, sink), 5)
+        del s_buf, d_buf
+        extra["calibration"] = {"valu_tnn_mix_tops_measured": valu_measured,
+                                "valu_bnn_mix_tops_measured": lb.lb_calib_valu_lane_instr(iters) / tv0 / 1e12,
+                                "valu_tops_published": VALU_PEAK_TOPS,
+                                "hbm_read_gbs": big / tr / 1e9, "hbm_write_gbs": big / tw / 1e9,
+                                "hbm_copy_gbs_read_plus_write": 2 * big / tc / 1e9, "hbm_gbs_published": HBM_PEAK_GBS}
+        out["roofline"]["frac_of_measured_valu_rate"] = achieved / valu_measured
         tpa = dev_time(lambda: lb.pack_ternary(dA, M, K, K, 1, Ap), 50)
         tpb = dev_time(lambda: lb.pack_ternary(dB, N, K, 1, N, Bp), 50)
         extra["pack_a_us"] = tpa * 1e6

@@ -172,6 +172,22 @@ LB_API int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64
                         int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * Calibration kernels for the benchmark: what the machine sustains for the two bounds of the rooflines.  The
+ * caller times them (HIP events on `stream`).
+ *   lb_calib_valu     runs lb_calib_valu_lane_instr(iters) lane-instructions of independent chains on registers with
+ *                     every wave slot of the device occupied; mix 0: the binary kernel's v_xor_b32 / v_bcnt_u32_b32
+ *                     pair, mix 1: the ternary kernel's v_and_b32 / v_bitop3_b32 / 2 x v_bcnt_u32_b32.
+ *   lb_calib_stream   mode 0: read `bytes` from src; 1: write `bytes` to dst; 2: copy src -> dst (128-bit accesses,
+ *                     bytes a multiple of 16; src / dst may be NULL for the mode that does not use them).
+ *   sink              device scratch owned by the caller, at least lb_calib_sink_bytes() bytes; receives per-thread
+ *                     results so that the work cannot be optimized away.
+ */
+LB_API size_t lb_calib_sink_bytes(void);
+LB_API int64_t lb_calib_valu_lane_instr(int64_t iters);
+LB_API int lb_calib_valu(int mix, int64_t iters, void *sink, void *stream);
+LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, void *sink, void *stream);
+
+/*
  * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
  *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
  *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel,

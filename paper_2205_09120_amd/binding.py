@@ -21,7 +21,7 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
-           "lb_variant_name")
+           "lb_variant_name", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
 
 class LowbitError(RuntimeError):
@@ -63,6 +63,14 @@ def lib() -> ctypes.CDLL:
         L.gemm_requant.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.gemm_u8_mfma.restype = ci
         L.gemm_u8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, ctypes.c_int32, ctypes.c_int32, vp, i64, vp]
+        L.lb_calib_sink_bytes.restype = ctypes.c_size_t
+        L.lb_calib_sink_bytes.argtypes = []
+        L.lb_calib_valu_lane_instr.restype = i64
+        L.lb_calib_valu_lane_instr.argtypes = [i64]
+        L.lb_calib_valu.restype = ci
+        L.lb_calib_valu.argtypes = [ci, i64, vp, vp]
+        L.lb_calib_stream.restype = ci
+        L.lb_calib_stream.argtypes = [ci, vp, vp, i64, vp, vp]
         L.lb_set_variant.restype = ci
         L.lb_set_variant.argtypes = [ci, ci]
         L.lb_num_variants.restype = ci
@@ -188,6 +196,22 @@ def gemm_u8_mfma(M, N, K, A, lda, B, ldb, zA: int, zB: int, C=None, ldc=None, st
         ldc = C.stride(0)
     _check(lib().gemm_u8_mfma(M, N, K, _ptr(A), lda, _ptr(B), ldb, zA, zB, _ptr(C), ldc, _stream(stream)))
     return C
+
+
+def lb_calib_sink_bytes() -> int:
+    return lib().lb_calib_sink_bytes()
+
+
+def lb_calib_valu_lane_instr(iters: int) -> int:
+    return lib().lb_calib_valu_lane_instr(iters)
+
+
+def lb_calib_valu(mix: int, iters: int, sink: torch.Tensor, stream=None) -> None:
+    _check(lib().lb_calib_valu(mix, iters, _ptr(sink), _stream(stream)))
+
+
+def lb_calib_stream(mode: int, src, dst, nbytes: int, sink, stream=None) -> None:
+    _check(lib().lb_calib_stream(mode, _ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream(stream)))
 
 
 def lb_set_variant(op, variant: int) -> None:

@@ -389,6 +389,41 @@ int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int6
     return LB_OK;
 }
 
+size_t lb_calib_sink_bytes(void) { return (size_t)lowbit::calib_grid_blocks() * 2 * 256 * 4; }
+
+int64_t lb_calib_valu_lane_instr(int64_t iters) { return iters > 0 ? lowbit::calib_valu_lane_instr(iters) : 0; }
+
+int lb_calib_valu(int mix, int64_t iters, void *sink, void *stream)
+{
+    if (mix != 0 && mix != 1)
+        return fail(LB_EINVAL, "lb_calib_valu: mix=%d must be 0 (xor, bcnt) or 1 (and, bitop3, bcnt, bcnt)", mix);
+    if (iters <= 0 || iters > (1 << 24))
+        return fail(LB_EINVAL, "lb_calib_valu: iters=%lld must lie in [1, 2^24]", (long long)iters);
+    if (!sink || !aligned(sink, 4))
+        return fail(LB_EINVAL, "lb_calib_valu: sink must be a 4-byte aligned device buffer");
+    const hipError_t e =
+        lowbit::launch_calib_valu(mix, (int)iters, static_cast<uint32_t *>(sink), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "lb_calib_valu: %s", hipGetErrorString(e));
+    return LB_OK;
+}
+
+int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, void *sink, void *stream)
+{
+    if (mode < 0 || mode > 2)
+        return fail(LB_EINVAL, "lb_calib_stream: mode=%d must be 0 (read), 1 (write) or 2 (copy)", mode);
+    if (bytes <= 0 || bytes % 16 != 0)
+        return fail(LB_EINVAL, "lb_calib_stream: bytes=%lld must be a positive multiple of 16", (long long)bytes);
+    if ((mode != 1 && (!src || !aligned(src, 16))) || (mode != 0 && (!dst || !aligned(dst, 16))) ||
+        (mode == 0 && (!sink || !aligned(sink, 4))))
+        return fail(LB_EINVAL, "lb_calib_stream: missing or misaligned buffer for mode %d", mode);
+    const hipError_t e = lowbit::launch_calib_stream(mode, src, dst, bytes, static_cast<uint32_t *>(sink),
+                                                     static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "lb_calib_stream: %s", hipGetErrorString(e));
+    return LB_OK;
+}
+
 int lb_set_variant(int op, int variant)
 {
     int count = 0;

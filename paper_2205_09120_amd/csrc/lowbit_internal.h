@@ -64,6 +64,12 @@ struct Im2colGeom {
 };
 hipError_t launch_im2col_packed(int planes, const uint64_t *Fp, uint64_t *Bp, const Im2colGeom &g, hipStream_t stream);
 
+// Calibration kernels (calibrate.hip).  sink needs calib_grid_blocks()*2*256 dwords.
+int calib_grid_blocks();
+int64_t calib_valu_lane_instr(int64_t iters);
+hipError_t launch_calib_valu(int mix, int iters, uint32_t *sink, hipStream_t stream);
+hipError_t launch_calib_stream(int mode, const void *src, void *dst, int64_t bytes, uint32_t *sink, hipStream_t stream);
+
 // int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream);

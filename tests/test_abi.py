@@ -119,6 +119,19 @@ def test_requant_argument_validation(L):
     assert f(0, 1, 0, 4, 64, None, None, None, None, None, None) == binding.LB_OK
 
 
+def test_calibration_argument_validation(L):
+    fake = 0x1000
+    assert L.lb_calib_sink_bytes() > 0
+    assert L.lb_calib_valu_lane_instr(1) > 0 and L.lb_calib_valu_lane_instr(0) == 0
+    assert L.lb_calib_valu(0, 0, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(0, 10, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(2, 10, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(3, fake, fake, 16, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(2, fake, fake, 15, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(0, None, None, 16, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(1, None, None, 16, None, None) == binding.LB_EINVAL
+
+
 def test_variant_hooks(L):
     for op in range(3):
         n = L.lb_num_variants(op)

@@ -335,3 +335,28 @@ def test_u8_extreme_values_and_depth_limit():
     with pytest.raises(lb.LowbitError) as e:
         lb.gemm_u8_mfma(70, 66, K + 1, dev(A), K + 1, dev(B), 66, 0, 255)
     assert e.value.status == lb.LB_EOVERFLOW
+
+
+# ------------------------------------------------------------------------------------------------ calibration kernels
+
+def test_calibration_kernels_run_and_copy_is_exact():
+    say("calibration kernels")
+    sink = torch.zeros(lb.lb_calib_sink_bytes() // 4, dtype=torch.int32, device="cuda")
+    lb.lb_calib_valu(1, 8, sink)
+    torch.cuda.synchronize()
+    assert sink.cpu().numpy()[: 2048 * 256].any()
+    lb.lb_calib_valu(0, 8, sink)
+    torch.cuda.synchronize()
+    # every thread accumulates popcounts of 8 * 16 32-bit words: 0 <= sum <= 8*16*32, and some are non-zero
+    s = sink.cpu().numpy()[: 2048 * 256]
+    assert s.min() >= 0 and s.max() <= 8 * 16 * 32 and s.any()
+    n = 1 << 20
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    lb.lb_calib_stream(2, src, dst, n, sink)
+    lb.lb_calib_stream(0, src, None, n, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    lb.lb_calib_stream(1, None, dst, n, sink)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint32)[:8], np.array([1, 2, 3, 4, 1, 2, 3, 4], dtype=np.uint32))
