@@ -137,13 +137,21 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
 #pragma unroll
             for (int t = 0; t < TV; ++t)
                 acc[a][i][t] = 0;
-    int32_t nnz[TV];
-#pragma unroll
-    for (int t = 0; t < TV; ++t)
-        nnz[t] = 0;
 
     // stage bookkeeping: unit u = wave*UPW + j covers V strings vseg*64 + lane at depth word g
     VVec pre[UPW];
+    // TBN needs the number of non-zeros of every V string (eq. (7)).  Every wave of the workgroup reads the same V
+    // strings, so counting in the main loop would repeat the work WAVES times; instead each staged element is counted
+    // once, by the lane that stages it, and the partial counts meet in LDS after the main loop.
+    __shared__ int32_t nnz_lds[KIND == KIND_TBN ? NV : 1];
+    int32_t nnz_part[UPW];
+    if constexpr (KIND == KIND_TBN) {
+#pragma unroll
+        for (int j = 0; j < UPW; ++j)
+            nnz_part[j] = 0;
+        for (int e = threadIdx.x; e < NV; e += 64 * WAVES)
+            nnz_lds[e] = 0;
+    }
     auto fetch = [&](int kg0) {
 #pragma unroll
         for (int j = 0; j < UPW; ++j) {
@@ -162,7 +170,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         for (int j = 0; j < UPW; ++j) {
             const int u = wave * UPW + j;
             const int vseg = u / KG, g = u % KG;
-            lds[buf][g * STRIDE + vseg * 64 + lane] = to_nz_neg(pre[j]);
+            const VVec e = to_nz_neg(pre[j]);
+            lds[buf][g * STRIDE + vseg * 64 + lane] = e;
+            if constexpr (KIND == KIND_TBN) {
+                popc_acc(nnz_part[j], e.x);
+                popc_acc(nnz_part[j], e.y);
+            }
         }
     };
 
@@ -213,8 +226,6 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                         popc_acc(acc[1][i][t], u1);
                     }
                 } else {
-                    popc_acc(nnz[t], b.x);
-                    popc_acc(nnz[t], b.y);
 #pragma unroll
                     for (int i = 0; i < TS; ++i) {
                         popc_acc(acc[0][i][t], xor_and_svv(sv[i].x, b.z, b.x));
@@ -262,8 +273,6 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                             popc_acc(acc[1][i][t], u1);
                         }
                     } else {
-                        popc_acc(nnz[t], bb.x);
-                        popc_acc(nnz[t], bb.y);
 #pragma unroll
                         for (int i = 0; i < TS; ++i) {
                             popc_acc(acc[0][i][t], xor_and_svv(sw[i].w[q * 2], bb.z, bb.x));
@@ -295,6 +304,20 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         if (c + 1 < nchunks)
             commit(buf ^ 1);
         __syncthreads();
+    }
+
+    int32_t nnz[TV];
+    if constexpr (KIND == KIND_TBN) {
+        // the main loop ended with a barrier, which also ordered the zero-fill of nnz_lds before these additions
+#pragma unroll
+        for (int j = 0; j < UPW; ++j) {
+            const int vseg = (wave * UPW + j) / KG;
+            atomicAdd(&nnz_lds[vseg * 64 + lane], nnz_part[j]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < TV; ++t)
+            nnz[t] = nnz_lds[t * 64 + lane];
     }
 
     // epilogue: eq. (6) / (7), then either the int32 store or (transposed orientation only) re-quantization
@@ -405,7 +428,7 @@ const GemmVariant kTbn[] = {
     LB_VARIANT(1, KIND_TBN, 4, 1, 4, 16, 8),
     LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 4),
     LB_VARIANT(3, KIND_TBN, 8, 2, 8, 8, 4),
-    LB_VARIANT(0, KIND_TBN, 8, 4, 8, 4, 1),
+    LB_VARIANT(4, KIND_TBN, 8, 4, 8, 4, 1),
     LB_VARIANT(0, KIND_TBN, 8, 4, 4, 4, 4),
     LB_VARIANT(0, KIND_TBN, 8, 2, 4, 8, 4),
 };
