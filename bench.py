@@ -110,18 +110,30 @@ def grid_scenario(args, torch, lb, synth) -> int:
         return a.elapsed_time(b) * 1e-3 / (replays * per_graph)
 
     shapes = synth.paper_shape_grid()
+    packed = {k: [] for k in ("tnn", "tbn", "bnn")}
     for idx, (H, W, D) in enumerate(shapes):
         for kind in ("tnn", "tbn", "bnn"):
             A, B = synth.make_custom(kind, H, W, D, seed=1000 + idx)
             dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
             Ap, Bp = lb.pack_a(kind, dA), lb.pack_b(kind, dB)
+            packed[kind].append((Ap, Bp))
             C = torch.empty((H, W), dtype=torch.int32, device="cuda")
             times[kind].append(graph_time(lambda: lb.gemm(kind, H, W, D, Ap, Bp, C, W)))
             if kind == "tnn":
                 times["int8_mfma"].append(graph_time(lambda: lb.gemm_i8_mfma(H, W, D, dA, D, dB, W, C, W)))
     ratio = {b: {a: float(np.mean(np.array(times[b]) / np.array(times[a]))) for a in algos} for b in algos}
+    # the same 64 products as ONE grouped launch per operand class
+    grouped = {}
+    total_ops = float(sum(2 * H * W * D for (H, W, D) in shapes))
+    for kind in ("tnn", "tbn", "bnn"):
+        grp = lb.GemmGroup(kind, packed[kind], shapes)
+        t = graph_time(grp.run)
+        grouped[kind] = {"all_64_shapes_us": t * 1e6, "per_shape_us": t * 1e6 / len(shapes),
+                         "workgroups": grp.workgroups, "tops": total_ops / t / 1e12,
+                         "speedup_vs_one_launch_per_shape": float(np.sum(times[kind]) / t)}
     out = {"scenario": "paper shape grid (Section IV-B), 64 shapes, one GEMM per launch, pre-packed operands",
            "mean_time_us": {a: float(np.mean(times[a]) * 1e6) for a in algos},
+           "grouped_launch": grouped,
            "ratio_mean_Trow_over_Tcol": ratio,
            "paper_table3_on_cortex_a73": {"U8/TNN": 2.51, "U8/TBN": 2.60, "U8/BNN": 7.52, "TNN/BNN": 2.99,
                                           "TBN/BNN": 2.90, "TNN/TBN": 1.03}}

@@ -147,6 +147,41 @@ LB_API int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t 
                         const uint64_t *Bp, const int32_t *lo, const int32_t *hi, uint64_t *Out, void *stream);
 
 /*
+ * Grouped launch: `count` independent products C_p = A_p B_p of one operand class in ONE kernel launch.  The paper's
+ * evaluation multiplies many small matrices (Section IV-B: heights 72..360, widths 24..96, depths 128..512), each
+ * far too small to occupy this GPU, so a launch per product is bound by launch latency; a group shares one grid.
+ *
+ *   lb_gemm_problem   the arguments of one gemm_bnn / gemm_tnn / gemm_tbn call (device pointers, same rules).
+ *                     Problems with M == 0 or N == 0 are allowed and produce no work.  Output regions of different
+ *                     problems must not overlap.
+ *   gemm_grouped_table_bytes
+ *                     HOST computation: size in bytes of the launch table for these problems, 0 if an argument is
+ *                     invalid or the size overflows (lb_last_error() says which).
+ *   gemm_grouped_plan HOST computation, no HIP call: validates every problem as gemm_* would and writes the launch
+ *                     table into `table` (HOST memory, table_bytes >= gemm_grouped_table_bytes(...)); stores the
+ *                     grid size in *workgroups.  The table holds the device pointers and extents of the problems
+ *                     and one 32-bit entry per workgroup; it stays valid as long as those pointers do and may be
+ *                     reused for any number of launches.
+ *   gemm_grouped      enqueues the launch.  table_dev is a DEVICE copy of the planned table (the caller copies it,
+ *                     16-byte aligned, and keeps it alive until the work has finished); kind, count and workgroups
+ *                     must be the values the table was planned with (the kernel re-checks them against the table
+ *                     header and does nothing on a mismatch).  workgroups == 0 is a valid no-op.
+ * kind: 0 = BNN, 1 = TNN, 2 = TBN.  Every problem is cut into 16 x 64 output tiles (the small-problem instance of the
+ * single-product kernels), so the call suits many small products; one large product is better served by gemm_*.
+ */
+typedef struct lb_gemm_problem {
+    int64_t M, N, K;
+    const uint64_t *Ap;
+    const uint64_t *Bp;
+    int32_t *C;
+    int64_t ldc;
+} lb_gemm_problem;
+LB_API size_t gemm_grouped_table_bytes(int kind, int64_t count, const lb_gemm_problem *problems);
+LB_API int gemm_grouped_plan(int kind, int64_t count, const lb_gemm_problem *problems, void *table, size_t table_bytes,
+                             int64_t *workgroups);
+LB_API int gemm_grouped(int kind, int64_t count, const void *table_dev, int64_t workgroups, void *stream);
+
+/*
  * gemm_i8_mfma -- the same product C = A B from UNPACKED int8 operands with int32 accumulation on the
  * integer matrix cores.  It plays the role the 8-bit gemmlowp multiplication (U8, Section IV, Table II/III)
  * plays in the paper: the comparison point for the low-bit kernels.  Any int8 values are allowed.

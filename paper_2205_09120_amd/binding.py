@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional
+from typing import Optional, Sequence
 
 import torch
 
@@ -20,8 +20,15 @@ OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
 _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
-           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
+           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_grouped_table_bytes",
+           "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
+
+
+class GemmProblem(ctypes.Structure):
+    """lb_gemm_problem of the C header: one product of a grouped launch (device addresses as integers)."""
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("Ap", ctypes.c_void_p),
+                ("Bp", ctypes.c_void_p), ("C", ctypes.c_void_p), ("ldc", ctypes.c_int64)]
 
 
 class LowbitError(RuntimeError):
@@ -55,6 +62,12 @@ def lib() -> ctypes.CDLL:
         for f in (L.gemm_bnn, L.gemm_tnn, L.gemm_tbn):
             f.restype = ci
             f.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
+        L.gemm_grouped_table_bytes.restype = ctypes.c_size_t
+        L.gemm_grouped_table_bytes.argtypes = [ci, i64, vp]
+        L.gemm_grouped_plan.restype = ci
+        L.gemm_grouped_plan.argtypes = [ci, i64, vp, vp, ctypes.c_size_t, ctypes.POINTER(i64)]
+        L.gemm_grouped.restype = ci
+        L.gemm_grouped.argtypes = [ci, i64, vp, i64, vp]
         L.im2col_packed.restype = ci
         L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
         L.gemm_i8_mfma.restype = ci
@@ -177,6 +190,36 @@ def gemm_i8_mfma(M, N, K, A, lda, B, ldb, C=None, ldc=None, stream=None):
     return C
 
 
+def _problem_array(problems: Sequence[GemmProblem]):
+    return (GemmProblem * max(len(problems), 1))(*problems)
+
+
+def gemm_grouped_table_bytes(kind, problems: Sequence[GemmProblem]) -> int:
+    """Bytes of the launch table for these problems (0 with lb_last_error() set if they are invalid)."""
+    return lib().gemm_grouped_table_bytes(_OPS.get(kind, kind), len(problems), _problem_array(problems))
+
+
+def gemm_grouped_plan(kind, problems: Sequence[GemmProblem]):
+    """Host-side planning: returns (table as a uint8 CPU tensor, workgroups)."""
+    arr = _problem_array(problems)
+    nbytes = lib().gemm_grouped_table_bytes(_OPS.get(kind, kind), len(problems), arr)
+    wg = ctypes.c_int64(0)
+    if nbytes == 0:  # invalid problems: let the planning call report which rule they break
+        scratch = torch.zeros(16, dtype=torch.uint8)
+        _check(lib().gemm_grouped_plan(_OPS.get(kind, kind), len(problems), arr, scratch.data_ptr(), 16,
+                                       ctypes.byref(wg)))
+        raise LowbitError(LB_EINVAL, "gemm_grouped_table_bytes returned 0")
+    table = torch.zeros(nbytes, dtype=torch.uint8)
+    _check(lib().gemm_grouped_plan(_OPS.get(kind, kind), len(problems), arr, table.data_ptr(), nbytes,
+                                   ctypes.byref(wg)))
+    return table, wg.value
+
+
+def gemm_grouped(kind, count: int, table_dev: Optional[torch.Tensor], workgroups: int, stream=None) -> None:
+    """Launch a planned group; table_dev is the device copy of the table gemm_grouped_plan returned."""
+    _check(lib().gemm_grouped(_OPS.get(kind, kind), count, _ptr(table_dev), workgroups, _stream(stream)))
+
+
 def gemm_requant(kind, out_planes: int, M, N, K, Ap, Bp, lo, hi=None, Out=None, stream=None):
     """Thresholded product written as N packed strings of depth M (1 = binary, 2 = ternary planes)."""
     if Out is None:
@@ -243,6 +286,27 @@ def pack_b(kind: str, B: torch.Tensor, stream=None) -> torch.Tensor:
     assert B.dtype == torch.int8 and B.stride(1) == 1
     f = pack_ternary if kind == "tnn" else pack_binary
     return f(B, N, K, 1, B.stride(0), stream=stream)
+
+
+class GemmGroup:
+    """A planned grouped launch: holds the operands, outputs and the device copy of the launch table."""
+
+    def __init__(self, kind: str, packed_pairs, shapes, Cs=None):
+        """packed_pairs: [(Ap, Bp)], shapes: [(M, N, K)]; Cs: optional list of int32 (M, >=N) tensors."""
+        self.kind, self.shapes = kind, list(shapes)
+        self.operands = list(packed_pairs)
+        dev = self.operands[0][0].device if self.operands else torch.device("cuda")
+        self.Cs = list(Cs) if Cs is not None else [torch.empty((M, N), dtype=torch.int32, device=dev)
+                                                   for (M, N, K) in self.shapes]
+        probs = [GemmProblem(M, N, K, _ptr(Ap) or None, _ptr(Bp) or None, _ptr(C) or None,
+                             C.stride(0) if C.dim() == 2 and C.numel() else max(N, 1))
+                 for (M, N, K), (Ap, Bp), C in zip(self.shapes, self.operands, self.Cs)]
+        table, self.workgroups = gemm_grouped_plan(kind, probs)
+        self.table_dev = table.to(dev)
+
+    def run(self, stream=None):
+        gemm_grouped(self.kind, len(self.shapes), self.table_dev, self.workgroups, stream)
+        return self.Cs
 
 
 def gemm(kind: str, M, N, K, Ap, Bp, C=None, ldc=None, stream=None):

@@ -97,9 +97,12 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
     return best >= 0 ? best : fallback;
 }
 
-int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
-            int32_t *C, int64_t ldc, void *stream)
+// Argument rules common to gemm_bnn / gemm_tnn / gemm_tbn and to every problem of a grouped launch.
+// *empty is set when there is nothing to compute (M == 0 or N == 0).
+int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
+               const int32_t *C, int64_t ldc, bool *empty)
 {
+    *empty = false;
     if (M < 0 || N < 0)
         return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
     if (K <= 0)
@@ -108,8 +111,10 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
         return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 2^31-1 (int32 accumulators)", name, (long long)K);
     if (M > kMaxExtent || N > kMaxExtent)
         return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
-    if (M == 0 || N == 0)
+    if (M == 0 || N == 0) {
+        *empty = true;
         return LB_OK;
+    }
     if (!Ap || !Bp || !C)
         return fail(LB_EINVAL, "%s: null pointer", name);
     if (ldc < N)
@@ -118,9 +123,22 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
         return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
     if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, 4))
         return fail(LB_EINVAL, "%s: operands must be 16-byte aligned, C 4-byte aligned", name);
+    return LB_OK;
+}
+
+// Which operand rides in scalar registers.  TBN: always the binary one (one scalar source per instruction), so lanes
+// own rows of C.  BNN / TNN: lanes own columns of C (coalesced stores) unless N is too narrow to fill a wavefront and
+// M is not.
+bool b_on_scalar_side(int kind, int64_t M, int64_t N) { return kind == lowbit::KIND_TBN || (N < 64 && M > N); }
+
+int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
+            int32_t *C, int64_t ldc, void *stream)
+{
+    bool empty;
+    const int rc = check_gemm(name, M, N, K, Ap, Bp, C, ldc, &empty);
+    if (rc != LB_OK || empty)
+        return rc;
     const int64_t KW = (K + 63) / 64;
-    if (KW > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: K too large", name);
 
     int count = 0;
     const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
@@ -149,29 +167,17 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
         }
     }
     lowbit::GemmArgs a;
-    bool transposed;
-    if (kind == lowbit::KIND_TBN) {
-        // the binary operand rides in scalar registers (one scalar source per instruction), the ternary one in
-        // vector registers: lanes own rows of C
+    const bool transposed = b_on_scalar_side(kind, M, N);
+    if (transposed) {
         a.Sp = reinterpret_cast<const uint32_t *>(Bp);
         a.rowsS = (int)N;
         a.Vp = reinterpret_cast<const uint32_t *>(Ap);
         a.rowsV = (int)M;
-        transposed = true;
     } else {
-        // lanes own columns of C (coalesced stores) unless N is too narrow to fill a wavefront and M is not
-        transposed = (N < 64 && M > N);
-        if (transposed) {
-            a.Sp = reinterpret_cast<const uint32_t *>(Bp);
-            a.rowsS = (int)N;
-            a.Vp = reinterpret_cast<const uint32_t *>(Ap);
-            a.rowsV = (int)M;
-        } else {
-            a.Sp = reinterpret_cast<const uint32_t *>(Ap);
-            a.rowsS = (int)M;
-            a.Vp = reinterpret_cast<const uint32_t *>(Bp);
-            a.rowsV = (int)N;
-        }
+        a.Sp = reinterpret_cast<const uint32_t *>(Ap);
+        a.rowsS = (int)M;
+        a.Vp = reinterpret_cast<const uint32_t *>(Bp);
+        a.rowsV = (int)N;
     }
     a.KW = (int)KW;
     a.K = (int)K;
@@ -183,6 +189,46 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;
+}
+
+
+// Validates every problem of a group and counts the workgroups the launch needs.
+int group_workgroups(int kind, const char *name, int64_t count, const lb_gemm_problem *problems, int64_t *workgroups)
+{
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    if (count < 0 || (count > 0 && !problems))
+        return fail(LB_EINVAL, "%s: count=%lld with problems=%p", name, (long long)count, (const void *)problems);
+    if (count > 0x7fffffffLL)
+        return fail(LB_EOVERFLOW, "%s: count=%lld exceeds 2^31-1", name, (long long)count);
+    int64_t total = 0;
+    for (int64_t p = 0; p < count; ++p) {
+        const lb_gemm_problem &q = problems[p];
+        bool empty;
+        char where[48];
+        snprintf(where, sizeof(where), "%s: problem %lld", name, (long long)p);
+        const int rc = check_gemm(where, q.M, q.N, q.K, q.Ap, q.Bp, q.C, q.ldc, &empty);
+        if (rc != LB_OK)
+            return rc;
+        if (empty)
+            continue;
+        const bool tr = b_on_scalar_side(kind, q.M, q.N);
+        const int64_t rowsS = tr ? q.N : q.M, rowsV = tr ? q.M : q.N;
+        total += ((rowsS + lowbit::kGroupTileS - 1) / lowbit::kGroupTileS) *
+                 ((rowsV + lowbit::kGroupTileV - 1) / lowbit::kGroupTileV);
+        if (total > 0x7fffffffLL)
+            return fail(LB_EOVERFLOW, "%s: more than 2^31-1 workgroups", name);
+    }
+    *workgroups = total;
+    return LB_OK;
+}
+
+size_t group_table_bytes(int64_t count, int64_t workgroups)
+{
+    // header + records + one entry per workgroup, rounded up to 16 bytes
+    const size_t raw = sizeof(lowbit::GroupHeader) + (size_t)count * sizeof(lowbit::GroupRecord) +
+                       (size_t)workgroups * sizeof(uint32_t);
+    return (raw + 15) & ~(size_t)15;
 }
 
 }  // namespace
@@ -225,6 +271,87 @@ int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t
              void *stream)
 {
     return do_gemm(lowbit::KIND_TBN, "gemm_tbn", M, N, K, Ap, Bp, C, ldc, stream);
+}
+
+size_t gemm_grouped_table_bytes(int kind, int64_t count, const lb_gemm_problem *problems)
+{
+    int64_t wg = 0;
+    if (group_workgroups(kind, "gemm_grouped_table_bytes", count, problems, &wg) != LB_OK)
+        return 0;
+    return group_table_bytes(count, wg);
+}
+
+int gemm_grouped_plan(int kind, int64_t count, const lb_gemm_problem *problems, void *table, size_t table_bytes,
+                      int64_t *workgroups)
+{
+    const char *name = "gemm_grouped_plan";
+    if (!table || !workgroups)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    int64_t wg = 0;
+    const int rc = group_workgroups(kind, name, count, problems, &wg);
+    if (rc != LB_OK)
+        return rc;
+    const size_t need = group_table_bytes(count, wg);
+    if (table_bytes < need)
+        return fail(LB_EINVAL, "%s: table_bytes=%zu < %zu", name, table_bytes, need);
+    memset(table, 0, need);
+    auto *hdr = static_cast<lowbit::GroupHeader *>(table);
+    auto *recs = reinterpret_cast<lowbit::GroupRecord *>(hdr + 1);
+    auto *owner = reinterpret_cast<uint32_t *>(recs + count);
+    hdr->magic = lowbit::kGroupMagic;
+    hdr->kind = (uint32_t)kind;
+    hdr->count = (uint32_t)count;
+    hdr->workgroups = (uint32_t)wg;
+    uint32_t next = 0;
+    for (int64_t p = 0; p < count; ++p) {
+        const lb_gemm_problem &q = problems[p];
+        lowbit::GroupRecord &r = recs[p];
+        r.tile0 = next;
+        if (q.M == 0 || q.N == 0)
+            continue;  // owns no workgroup; the zeroed record is never read
+        const bool tr = b_on_scalar_side(kind, q.M, q.N);
+        r.Sp = reinterpret_cast<const uint32_t *>(tr ? q.Bp : q.Ap);
+        r.Vp = reinterpret_cast<const uint32_t *>(tr ? q.Ap : q.Bp);
+        r.C = q.C;
+        r.ldc = q.ldc;
+        r.rowsS = (int32_t)(tr ? q.N : q.M);
+        r.rowsV = (int32_t)(tr ? q.M : q.N);
+        r.KW = (int32_t)((q.K + 63) / 64);
+        r.K = (int32_t)q.K;
+        r.nSB = (r.rowsS + lowbit::kGroupTileS - 1) / lowbit::kGroupTileS;
+        r.transposed = tr ? 1 : 0;
+        const uint32_t tiles = (uint32_t)r.nSB * (uint32_t)((r.rowsV + lowbit::kGroupTileV - 1) / lowbit::kGroupTileV);
+        for (uint32_t t = 0; t < tiles; ++t)
+            owner[next + t] = (uint32_t)p;
+        next += tiles;
+    }
+    *workgroups = wg;
+    return LB_OK;
+}
+
+int gemm_grouped(int kind, int64_t count, const void *table_dev, int64_t workgroups, void *stream)
+{
+    const char *name = "gemm_grouped";
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    if (count < 0 || workgroups < 0)
+        return fail(LB_EINVAL, "%s: count=%lld workgroups=%lld must be >= 0", name, (long long)count,
+                    (long long)workgroups);
+    if (count > 0x7fffffffLL || workgroups > 0x7fffffffLL)
+        return fail(LB_EOVERFLOW, "%s: count=%lld workgroups=%lld exceed 2^31-1", name, (long long)count,
+                    (long long)workgroups);
+    if (workgroups == 0)
+        return LB_OK;
+    if (count == 0)
+        return fail(LB_EINVAL, "%s: %lld workgroups for no problems", name, (long long)workgroups);
+    if (!table_dev || !aligned(table_dev, 16))
+        return fail(LB_EINVAL, "%s: table_dev must be a 16-byte aligned device pointer", name);
+    const hipError_t e =
+        lowbit::launch_gemm_group(kind, static_cast<const lowbit::GroupHeader *>(table_dev), (uint32_t)count,
+                                  (uint32_t)workgroups, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
 }
 
 int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,

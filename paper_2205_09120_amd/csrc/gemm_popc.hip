@@ -84,14 +84,25 @@ template <int N> struct alignas(4) Words { uint32_t w[N]; };
 
 template <int N> using IntC = std::integral_constant<int, N>;
 
-template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
-__global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
-                                                               const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
-                                                               int KW, int K, int32_t *__restrict__ C, int64_t ldc,
-                                                               int nSB, int nVB, int tiles_per_xcd,
-                                                               const int32_t *__restrict__ q_lo,
-                                                               const int32_t *__restrict__ q_hi,
-                                                               uint64_t *__restrict__ q_out, int q_planes)
+// LDS needs of one workgroup tile, shared by the kernels below and the tile routine.
+template <int KIND, int TV, int KG> struct TileLds {
+    using VVec = typename Vec<Traits<KIND>::VD>::type;
+    static constexpr int NV = 64 * TV;
+    static constexpr int STRIDE = NV + kPadEntries;
+    static constexpr int STAGE = KG * STRIDE;                     // entries of one staging buffer
+    static constexpr int NNZ = KIND == KIND_TBN ? NV : 1;          // per-string non-zero counts (TBN only)
+};
+
+// One workgroup tile: S block sb, V block vb of the problem described by the arguments.  TRM selects where product
+// (s, v) goes: 0 -> C[s*ldc + v], 1 -> C[v*ldc + s] (or the re-quantized output), 2 -> decided by tr_rt at run time
+// (workgroup-uniform), for launches that mix both orientations.
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG, int TRM>
+__device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, const uint32_t *__restrict__ Vp,
+                                               int rowsS, int rowsV, int KW, int K, int32_t *__restrict__ C,
+                                               int64_t ldc, int sb, int vb, bool tr_rt,
+                                               const int32_t *__restrict__ q_lo, const int32_t *__restrict__ q_hi,
+                                               uint64_t *__restrict__ q_out, int q_planes,
+                                               typename TileLds<KIND, TV, KG>::VVec *lds_base, int32_t *nnz_lds)
 {
     using T = Traits<KIND>;
     constexpr int SD = T::SD, VD = T::VD;
@@ -102,16 +113,10 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
     constexpr int UNITS = TV * KG;            // wave-wide loads per stage
     static_assert(UNITS % WAVES == 0, "stage units must divide among the waves");
     constexpr int UPW = UNITS / WAVES;        // per wave
+    const bool tr = TRM == 2 ? tr_rt : (TRM == 1);
 
-    __shared__ VVec lds[2][KG * STRIDE];
+    VVec(*lds)[KG * STRIDE] = reinterpret_cast<VVec(*)[KG * STRIDE]>(lds_base);  // two staging buffers
 
-    // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give each XCD a contiguous
-    // range of tiles; within it the S blocks of one V tile are adjacent and share that XCD's L2.
-    const int bid = blockIdx.x;
-    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
-    if ((bid >> 3) >= tiles_per_xcd || idx >= nSB * nVB)
-        return;
-    const int vb = idx / nSB, sb = idx - vb * nSB;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int s0 = (sb * WAVES + wave) * TS;
@@ -143,7 +148,6 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
     // TBN needs the number of non-zeros of every V string (eq. (7)).  Every wave of the workgroup reads the same V
     // strings, so counting in the main loop would repeat the work WAVES times; instead each staged element is counted
     // once, by the lane that stages it, and the partial counts meet in LDS after the main loop.
-    __shared__ int32_t nnz_lds[KIND == KIND_TBN ? NV : 1];
     int32_t nnz_part[UPW];
     if constexpr (KIND == KIND_TBN) {
 #pragma unroll
@@ -334,7 +338,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
             else
                 out[i] = nnz[t] - 2 * acc[0][i][t];
         }
-        if constexpr (TR) {
+        if (tr) {
             if (q_out != nullptr) {
                 // Lanes own 64 consecutive V rows (channels), so a wave-wide vote on "c > hi" / "c < lo" is exactly one
                 // 64-bit depth word of the packed output string of S row s0+i.  Lane 0 stores it.
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
             }
         }
         if (v < rowsV) {
-            if constexpr (!TR) {
+            if (!tr) {
 #pragma unroll
                 for (int i = 0; i < TS; ++i)
                     if (s0 + i < rowsS)
@@ -381,6 +385,56 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
             }
         }
     }
+}
+
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
+__global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
+                                                               const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
+                                                               int KW, int K, int32_t *__restrict__ C, int64_t ldc,
+                                                               int nSB, int nVB, int tiles_per_xcd,
+                                                               const int32_t *__restrict__ q_lo,
+                                                               const int32_t *__restrict__ q_hi,
+                                                               uint64_t *__restrict__ q_out, int q_planes)
+{
+    using L = TileLds<KIND, TV, KG>;
+    __shared__ typename L::VVec lds[2 * L::STAGE];
+    __shared__ int32_t nnz_lds[L::NNZ];
+
+    // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give each XCD a contiguous
+    // range of tiles; within it the S blocks of one V tile are adjacent and share that XCD's L2.
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nSB * nVB)
+        return;
+    const int vb = idx / nSB, sb = idx - vb * nSB;
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, K, C, ldc, sb, vb, TR, q_lo, q_hi,
+                                                            q_out, q_planes, lds, nnz_lds);
+}
+
+// Grouped launch: many independent small problems in one grid.  The table (built on the host by plan_group) maps
+// each workgroup id to a problem record and the record gives the tile's place inside that problem.
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
+__global__ __launch_bounds__(64 * WAVES) void gemm_group_kernel(const GroupHeader *__restrict__ table, uint32_t count)
+{
+    using L = TileLds<KIND, TV, KG>;
+    __shared__ typename L::VVec lds[2 * L::STAGE];
+    __shared__ int32_t nnz_lds[L::NNZ];
+
+    // A table that was planned for another kind, problem count or grid is not read any further.
+    const uint32_t bid = blockIdx.x;
+    if (table->magic != kGroupMagic || table->kind != (uint32_t)KIND || table->count != count ||
+        table->workgroups != gridDim.x)
+        return;
+    const GroupRecord *__restrict__ recs = reinterpret_cast<const GroupRecord *>(table + 1);
+    const uint32_t *__restrict__ owner = reinterpret_cast<const uint32_t *>(recs + count);
+    const uint32_t p = owner[bid];
+    if (p >= count)
+        return;
+    const GroupRecord r = recs[p];
+    const int local = (int)(bid - r.tile0);
+    const int vb = local / r.nSB, sb = local - vb * r.nSB;
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 2>(r.Sp, r.Vp, r.rowsS, r.rowsV, r.KW, r.K, r.C, r.ldc, sb, vb,
+                                                   r.transposed != 0, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
 }
 
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
@@ -434,6 +488,30 @@ const GemmVariant kTbn[] = {
 };
 
 }  // namespace
+
+hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
+                             hipStream_t stream)
+{
+    // the small-problem instances (first row of each table above): 4 waves x 4 strings by 64 strings per workgroup
+    static_assert(kGroupTileS == 4 * 4 && kGroupTileV == 64, "group tile = small-problem instance");
+    switch (kind) {
+    case KIND_BNN:
+        hipLaunchKernelGGL((gemm_group_kernel<KIND_BNN, 4, 1, 4, 16, 8>), dim3(workgroups), dim3(256), 0, stream,
+                           table_dev, count);
+        break;
+    case KIND_TNN:
+        hipLaunchKernelGGL((gemm_group_kernel<KIND_TNN, 4, 1, 4, 16, 4>), dim3(workgroups), dim3(256), 0, stream,
+                           table_dev, count);
+        break;
+    case KIND_TBN:
+        hipLaunchKernelGGL((gemm_group_kernel<KIND_TBN, 4, 1, 4, 16, 8>), dim3(workgroups), dim3(256), 0, stream,
+                           table_dev, count);
+        break;
+    default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
 
 const GemmVariant *gemm_variants(int kind, int *count)
 {

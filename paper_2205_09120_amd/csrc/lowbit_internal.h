@@ -37,6 +37,32 @@ struct GemmVariant {
 
 const GemmVariant *gemm_variants(int kind, int *count);
 
+// Grouped launch: one grid covers `count` independent problems, each cut into kGroupTileS x kGroupTileV tiles.
+// The table is header, `count` records, then one uint32 per workgroup naming the record that owns it; it is built on
+// the host (api.hip), copied to the device by the caller and read by the kernel.
+constexpr int kGroupTileS = 16, kGroupTileV = 64;
+constexpr uint32_t kGroupMagic = 0x4c424754u;  // "LBGT"
+struct GroupHeader {
+    uint32_t magic;
+    uint32_t kind;
+    uint32_t count;
+    uint32_t workgroups;
+};
+struct GroupRecord {
+    const uint32_t *Sp;  // scalar-side operand, rowsS strings
+    const uint32_t *Vp;  // vector-side operand, rowsV strings
+    int32_t *C;
+    int64_t ldc;
+    int32_t rowsS, rowsV, KW, K;
+    int32_t nSB;         // tiles along S; tile t of the problem is (vb, sb) = (t / nSB, t % nSB)
+    uint32_t tile0;      // first workgroup of the problem
+    int32_t transposed;  // 0: product (s, v) -> C[s*ldc + v]; 1: -> C[v*ldc + s]
+    int32_t reserved;
+};
+static_assert(sizeof(GroupHeader) == 16 && sizeof(GroupRecord) == 64, "table layout is part of the host/device contract");
+hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
+                             hipStream_t stream);
+
 // Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8
 // strings at a time).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.
 // Operand classes per kind: BNN X,Y binary; TNN X,Y ternary; TBN X ternary, Y binary.

@@ -154,3 +154,66 @@ def test_binding_raises_with_message(L):
     with pytest.raises(binding.LowbitError) as e:
         binding._check(L.gemm_tnn(4, 8, 64, 0x1000, 0x1000, 0x1000, 7, None))
     assert e.value.status == binding.LB_EINVAL and "ldc" in str(e.value)
+
+
+def test_grouped_planning_is_host_logic(L):
+    """gemm_grouped_plan runs without a GPU: the table it writes is checked against its documented structure."""
+    import numpy as np
+    P = binding.GemmProblem
+    probs = [P(72, 24, 128, 0x1000, 0x2000, 0x3000, 24),    # narrow N: B rides on the scalar side (transposed)
+             P(0, 5, 64, None, None, None, 5),               # empty: owns no workgroup
+             P(100, 96, 512, 0x4000, 0x5000, 0x6000, 100)]   # lanes own columns
+    for kind, want_tr in (("bnn", [1, 0]), ("tnn", [1, 0]), ("tbn", [1, 1])):
+        table, wg = binding.gemm_grouped_plan(kind, probs)
+        assert table.numel() == binding.gemm_grouped_table_bytes(kind, probs) and table.numel() % 16 == 0
+        raw = table.numpy()
+        magic, k, count, total = raw[:16].view(np.uint32)
+        assert (magic, k, count, total) == (0x4C424754, binding._OPS[kind], 3, wg)
+        recs = raw[16:16 + 64 * 3].view(np.int32).reshape(3, 16)
+        owner = raw[16 + 64 * 3:16 + 64 * 3 + 4 * wg].view(np.uint32)
+        live = [recs[0], recs[2]]
+        tiles = []
+        for r, tr, (M, N, K, a, b) in zip(live, want_tr, [(72, 24, 128, 0x1000, 0x2000), (100, 96, 512, 0x4000, 0x5000)]):
+            rowsS, rowsV = (N, M) if tr else (M, N)
+            assert r[14] == tr and (r[8], r[9], r[10], r[11]) == (rowsS, rowsV, (K + 63) // 64, K)
+            assert (r[0], r[2]) == ((b, a) if tr else (a, b))
+            assert r[12] == -(-rowsS // 16)
+            tiles.append(int(r[12]) * -(-rowsV // 64))
+        assert wg == sum(tiles)
+        assert recs[0][13] == 0 and recs[1][13] == tiles[0] and recs[2][13] == tiles[0]
+        assert list(owner) == [0] * tiles[0] + [2] * tiles[1]
+
+
+def test_grouped_argument_validation(L):
+    P = binding.GemmProblem
+    ok = P(8, 8, 64, 0x1000, 0x2000, 0x3000, 8)
+    for bad in (P(8, 8, 0, 0x1000, 0x2000, 0x3000, 8), P(8, 8, 64, None, 0x2000, 0x3000, 8),
+                P(8, 8, 64, 0x1000, 0x2000, 0x3000, 7), P(-1, 8, 64, 0x1000, 0x2000, 0x3000, 8),
+                P(8, 8, 64, 0x1008, 0x2000, 0x3000, 8)):
+        assert binding.gemm_grouped_table_bytes("tnn", [ok, bad]) == 0
+        assert b"problem 1" in L.lb_last_error()
+        with pytest.raises(binding.LowbitError) as e:
+            binding.gemm_grouped_plan("tnn", [ok, bad])
+        assert e.value.status == binding.LB_EINVAL
+    with pytest.raises(binding.LowbitError) as e:
+        binding.gemm_grouped_plan("tnn", [P(8, 8, 2 ** 31, 0x1000, 0x2000, 0x3000, 8)])
+    assert e.value.status == binding.LB_EOVERFLOW
+    assert binding.gemm_grouped_table_bytes(3, [ok]) == 0
+    # too small a table buffer, null outputs
+    arr = (P * 1)(ok)
+    buf = ctypes.create_string_buffer(64)
+    wg = ctypes.c_int64(0)
+    assert L.gemm_grouped_plan(1, 1, arr, buf, 64, ctypes.byref(wg)) == binding.LB_EINVAL
+    assert L.gemm_grouped_plan(1, 1, arr, None, 4096, ctypes.byref(wg)) == binding.LB_EINVAL
+    assert L.gemm_grouped_plan(1, 1, None, buf, 64, ctypes.byref(wg)) == binding.LB_EINVAL
+    # launch call: everything is checked before the first HIP call
+    assert L.gemm_grouped(1, 0, None, 0, None) == binding.LB_OK
+    assert L.gemm_grouped(5, 1, 0x1000, 1, None) == binding.LB_EINVAL
+    assert L.gemm_grouped(1, 1, None, 1, None) == binding.LB_EINVAL
+    assert L.gemm_grouped(1, 1, 0x1004, 1, None) == binding.LB_EINVAL
+    assert L.gemm_grouped(1, 0, 0x1000, 1, None) == binding.LB_EINVAL
+    assert L.gemm_grouped(1, -1, 0x1000, 1, None) == binding.LB_EINVAL
+    assert L.gemm_grouped(1, 1, 0x1000, 2 ** 31, None) == binding.LB_EOVERFLOW
+    # an empty group plans to a header-only table
+    table, wg2 = binding.gemm_grouped_plan("bnn", [])
+    assert wg2 == 0 and table.numel() == 16
