@@ -393,6 +393,13 @@ def main() -> int:
         out["cpu_baseline"] = {"value": 2.0 * rows * N * K / dt / 1e12, "unit": "TOPS", "cores": used,
                                "kind": "oracle",
                                "sample": f"first {rows} of {M} rows of A against the full B ({dt:.1f} s of CPU time)"}
+        # the same oracle on one thread (last: the thread count set here stays in force for later calls)
+        rows1 = int(min(M, max(8, rows * 3 // max(used, 1))))
+        t0 = time.perf_counter()
+        oracle.gemm_threads(np.ascontiguousarray(A[:rows1]), B, threads=1)
+        dt1 = time.perf_counter() - t0
+        out["cpu_baseline"]["single_thread"] = {"value": 2.0 * rows1 * N * K / dt1 / 1e12, "unit": "TOPS",
+                                                "sample": f"first {rows1} rows ({dt1:.1f} s)"}
     print(json.dumps(out), flush=True)
     return 0
 

@@ -3,28 +3,30 @@
 // Comparison point for the popcount kernels: it computes the same C = A B from unpacked int8 operands, the role
 // the 8-bit gemmlowp multiplication (U8) plays in Section IV of the paper.
 //
-// Workgroup = 4 waves in a 2 x 2 arrangement; a wave computes TM x TN MFMA tiles of 32 x 32, so the workgroup
-// tile is (64*TM) x (64*TN); depth step 64 (two MFMA depth steps of 32).  Instances: 256 x 128 (TM=4, TN=2)
-// for large problems, 128 x 128 (TM=TN=2) for small ones, 256 x 256 selectable for experiments.
+// Two kernels share the tile layouts described here.  gemm_i8_mfma_kernel: workgroup = 4 waves in a 2 x 2
+// arrangement; a wave computes TM x TN MFMA tiles of 32 x 32, so the workgroup tile is (64*TM) x (64*TN); depth step
+// 64 (two MFMA depth steps of 32); instances 128 x 128 (TM=TN=2, the default for small and ragged problems),
+// 256 x 128 and 256 x 256 (selectable).  gemm_i8_ws_kernel (further down): the 256 x 128 tile with the loading and
+// the multiplying done by different waves, the default for large problems.
 //   A (row-major, depth contiguous) is staged as is:  As[row][64 depth bytes (+16 pad)]; an operand fragment
 //   (16 depth bytes of one row per lane) is one ds_read_b128, conflict-free with the 80-byte row stride.
 //   B (row-major, depth strided) is transposed on the way: a thread loads 16 depth rows x 4 columns (16 dwords,
 //   each wave-wide load is contiguous along the columns), transposes 4x4 byte blocks in registers (v_perm_b32)
 //   and stores, per column, the 16 consecutive depth bytes an MFMA lane needs:
-//   Bs[depth block of 16][column%4][column/4][16 bytes] (+32 bytes pad per column%4 plane), so that both the
-//   ds_write_b128 of the staging and the ds_read_b128 of the fragments are bank-conflict free.
+//   Bs[depth block of 16][column%4][column/4][16 bytes] (+64 bytes pad per column%4 plane, so that the four
+//   planes start 16 banks apart): the ds_write_b128 of the staging and the ds_read_b128 of the fragments both
+//   spread over all banks.
 // Both MFMA operands take 16 depth bytes per lane (lane%32 = row / column, lane/32 = which half of the 32 deep
 // step); A and B use the same slot order, so the order of depth positions inside the instruction is immaterial.
-// LDS is double buffered: the next depth step is fetched into registers while the current one is multiplied,
-// written to the other buffer afterwards, one barrier per step.  Measured on 1024 x 50176 x 4608 the 256 x 128
-// tile is the fastest of the three instances; the kernel is bound by the latency of the per-step global loads
-// (one step of prefetch, one wave per SIMD), not by the matrix cores.
+// LDS is double buffered: in the 4-wave kernel the next depth step is fetched into registers while the current one
+// is multiplied and written to the other buffer afterwards, one barrier per step.
 //
 // Unsigned 8-bit operands with zero points (U8 = true; eq. (2) and (3) of the paper, the gemmlowp scheme): the
-// bytes are re-biased to signed on the way in (x' = x - 128, one XOR), the matrix cores form sum a'b', and the
-// epilogue applies  C = sum a'b' - zB' * rowsum(a') - zA' * colsum(b') + K * zA' * zB'  with zA' = zA - 128,
-// zB' = zB - 128, which equals sum (a - zA)(b - zB).  Row and column sums are accumulated with packed dot products
-// by the threads that stage the tiles, and combined through LDS after the depth loop.
+// bytes are re-biased to signed on their way into LDS (x' = x - 128, one XOR), the matrix cores form sum a'b', and
+// the epilogue applies  C = sum a'b' - zB' * rowsum(a') - zA' * colsum(b') + K * zA' * zB'  with zA' = zA - 128,
+// zB' = zB - 128, which equals sum (a - zA)(b - zB).  Row and column sums are taken by the threads that stage the
+// tiles, as sums of the unsigned bytes (v_sad_u8 against zero, 4 bytes per instruction) minus 128 per byte, and
+// combined through LDS after the depth loop.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -52,10 +54,9 @@ __device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t o[4])
     o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-__device__ __forceinline__ int32_t bytesum(uint32_t x, int32_t c)
-{
-    return __builtin_amdgcn_sdot4((int)x, 0x01010101, c, false);
-}
+// c + sum of the four unsigned bytes of x, one full-rate instruction (the packed dot product that would add signed
+// bytes directly issues at a fraction of that rate and slowed the whole kernel down by a factor of two)
+__device__ __forceinline__ uint32_t bytesum(uint32_t x, uint32_t c) { return __builtin_amdgcn_sad_u8(x, 0u, c); }
 
 template <int TM, int TN, int MODE, bool U8>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_mfma_kernel(
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;  // unsigned byte -> signed byte minus 128
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int NQ = BN / 4;                       // column quads per tile
-    constexpr int B_PLANE = NQ * 16 + 32;            // bytes per (depth block, column%4) plane
+    constexpr int B_PLANE = NQ * 16 + 64;            // bytes per (depth block, column%4) plane
     constexpr int B_BLOCK = 4 * B_PLANE;             // bytes per depth block of 16
     constexpr int A_BYTES = BM * A_STRIDE, B_BYTES = 4 * B_BLOCK;
     constexpr int A_PT = BM * 4 / 256;               // uint4 loads of A per thread
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)(m0 + (u >> 2)) * lda + k0 + (u & 3) * 16);
             // four dwords assembled by value (the compiler merges them into one 128-bit load); copying the uint4
             // as an aggregate makes the optimiser keep a_pre in memory and demote it to LDS
-            a_pre[p] = make_uint4(src[0] ^ FLIP, src[1] ^ FLIP, src[2] ^ FLIP, src[3] ^ FLIP);
+            a_pre[p] = make_uint4(src[0], src[1], src[2], src[3]);
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const int8_t *src = B + (int64_t)(k0 + kb * 16) * ldb + n0 + nq * 4;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                b_pre[p][j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb) ^ FLIP;
+                b_pre[p][j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb);
         }
     };
     auto fetch_clamped = [&](int k0) __attribute__((always_inline)) {
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const bool ok = r < M && k + 16 <= K;
             const int rr = r < M ? r : M - 1, kk = k + 16 <= K ? k : K - 16;
             const uint4 v = *reinterpret_cast<const uint4 *>(A + (int64_t)rr * lda + kk);
-            a_pre[p] = ok ? make_uint4(v.x ^ FLIP, v.y ^ FLIP, v.z ^ FLIP, v.w ^ FLIP) : make_uint4(0u, 0u, 0u, 0u);
+            a_pre[p] = make_uint4(ok ? v.x : FLIP, ok ? v.y : FLIP, ok ? v.z : FLIP, ok ? v.w : FLIP);
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 const int k = k0 + kb * 16 + j;
                 const int kk = k < K ? k : K - 1;
                 const uint32_t x = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
-                b_pre[p][j] = (k < K && n + 4 <= N) ? (x ^ FLIP) : 0u;
+                b_pre[p][j] = (k < K && n + 4 <= N) ? x : FLIP;
             }
         }
     };
@@ -144,10 +145,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
             const int r = m0 + (u >> 2), k = k0 + (u & 3) * 16;
-            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            uint32_t w[4] = {FLIP, FLIP, FLIP, FLIP};
             if (r < M)
                 for (int i = 0; i < 16 && k + i < K; ++i)
-                    w[i >> 2] |= (uint32_t)((uint8_t)A[(int64_t)r * lda + k + i] ^ (FLIP & 0xffu)) << (8 * (i & 3));
+                    w[i >> 2] ^= (uint32_t)((uint8_t)A[(int64_t)r * lda + k + i] ^ (FLIP & 0xffu)) << (8 * (i & 3));
             a_pre[p] = make_uint4(w[0], w[1], w[2], w[3]);
         }
 #pragma unroll
@@ -157,10 +158,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const int n = n0 + nq * 4;
             for (int j = 0; j < 16; ++j) {
                 const int k = k0 + kb * 16 + j;
-                uint32_t x = 0u;
+                uint32_t x = FLIP;
                 if (k < K)
                     for (int i = 0; i < 4 && n + i < N; ++i)
-                        x |= (uint32_t)((uint8_t)B[(int64_t)k * ldb + n + i] ^ (FLIP & 0xffu)) << (8 * i);
+                        x ^= (uint32_t)((uint8_t)B[(int64_t)k * ldb + n + i] ^ (FLIP & 0xffu)) << (8 * i);
                 b_pre[p][j] = x;
             }
         }
@@ -173,8 +174,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         else
             fetch_bytes(k0);
     };
-    // U8: signed sums of the staged bytes, per thread; the rows / columns a thread stages are the same in every step
-    int32_t rs_acc[A_PT], cs_acc[B_PT][4];
+    // U8: sums of the staged bytes as UNSIGNED values, per thread; the rows / columns a thread stages are the same in
+    // every step and every step adds exactly 16 bytes per sum (out-of-range bytes count as 128), so the sum of the
+    // re-biased signed bytes is the unsigned sum minus 128 * 16 * steps.
+    uint32_t rs_acc[A_PT], cs_acc[B_PT][4];
 #pragma unroll
     for (int p = 0; p < A_PT; ++p)
         rs_acc[p] = 0;
@@ -189,9 +192,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
-            *reinterpret_cast<uint4 *>(&As[(u >> 2) * A_STRIDE + (u & 3) * 16]) = a_pre[p];
+            const uint4 v = a_pre[p];
+            *reinterpret_cast<uint4 *>(&As[(u >> 2) * A_STRIDE + (u & 3) * 16]) =
+                make_uint4(v.x ^ FLIP, v.y ^ FLIP, v.z ^ FLIP, v.w ^ FLIP);
             if constexpr (U8)
-                rs_acc[p] = bytesum(a_pre[p].x, bytesum(a_pre[p].y, bytesum(a_pre[p].z, bytesum(a_pre[p].w, rs_acc[p]))));
+                rs_acc[p] = bytesum(v.x, bytesum(v.y, bytesum(v.z, bytesum(v.w, rs_acc[p]))));
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 *reinterpret_cast<uint4 *>(&Bs[kb * B_BLOCK + i * B_PLANE + nq * 16]) =
-                    make_uint4(o[0][i], o[1][i], o[2][i], o[3][i]);
+                    make_uint4(o[0][i] ^ FLIP, o[1][i] ^ FLIP, o[2][i] ^ FLIP, o[3][i] ^ FLIP);
                 if constexpr (U8)
                     cs_acc[p][i] = bytesum(o[0][i], bytesum(o[1][i], bytesum(o[2][i], bytesum(o[3][i], cs_acc[p][i]))));
             }
@@ -269,7 +274,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         static_assert((BM + BN) * 4 * 4 <= 2 * (A_BYTES + B_BYTES), "sums must fit the tile buffers");
 #pragma unroll
         for (int p = 0; p < A_PT; ++p)
-            rsum[tid + p * 256] = rs_acc[p];                      // unit u = row*4 + quarter
+            rsum[tid + p * 256] = (int32_t)rs_acc[p] - 2048 * nsteps;  // unit u = row*4 + quarter
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
             const int u = tid + p * 256;
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             const int kb = u / NQ, nq = u % NQ;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                csum[(nq * 4 + i) * 4 + kb] = cs_acc[p][i];
+                csum[(nq * 4 + i) * 4 + kb] = (int32_t)cs_acc[p][i] - 2048 * nsteps;
         }
         __syncthreads();
     }
@@ -301,6 +306,278 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 if constexpr (U8)
                     out += ccorr - zB * (rsum[lrow * 4] + rsum[lrow * 4 + 1] + rsum[lrow * 4 + 2] + rsum[lrow * 4 + 3]);
                 if (row < M && col < N)
+                    C[(int64_t)row * ldc + col] = out;
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Wave-specialised instance for large problems: 256 x 128 tile, 8 waves.
+//
+// The kernel above keeps one depth step of operands in flight per wave, and a wave that multiplies cannot afford the
+// registers for more (128 accumulator registers per lane); with a global-load latency several times the 0.2 us a
+// depth step takes on the matrix cores, the matrix cores wait.  Here the two jobs are split between waves of one
+// workgroup, two waves per SIMD:
+//   waves 0-3 (consumers)  only read operand fragments from LDS and issue MFMAs (2 x 2 arrangement, 128 x 64 outputs
+//                          each), fragment reads of the next half step overlapping the MFMAs of the current one;
+//   waves 4-5 (B loaders)  fetch B (depth-strided), transpose 4x4 byte blocks in registers and write the LDS layout
+//                          the fragments need;  waves 6-7 (A loaders) fetch and store A.
+// Loaders own no accumulators, so they keep DEPTH depth steps of loads in flight in registers.  LDS is double
+// buffered; barrier k (k = 0 .. steps-1) means "buffer k%2 holds depth step k".  A consumer finishes its reads of
+// step k before it arrives at barrier k+1, and a loader overwrites buffer k%2 (with step k+2) only after it has
+// passed barrier k+1, so two buffers suffice.  Barriers are a bare s_barrier after waiting for the wave's own LDS
+// operations only: a full __syncthreads() would also wait for the loaders' outstanding global loads and undo the
+// prefetch.  Unsigned operands: the loaders also form the row / column sums of eq. (3) (they have the registers to
+// spare), so the consumers' loop is the same as for signed operands.
+__device__ __forceinline__ void lds_barrier()
+{
+    // the scheduling fences keep register-only work (the byte transposes of a later step, MFMAs) on its side of the
+    // barrier: moved above it, a transpose would wait for loads that are meant to stay in flight
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) only; as a builtin, so that the compiler's own counting sees it
+    asm volatile("s_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int MODE, bool U8, int DEPTH>
+__global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, const int8_t *__restrict__ A, int64_t lda,
+                                                         const int8_t *__restrict__ B, int64_t ldb,
+                                                         int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB,
+                                                         int tiles_per_xcd, int zA, int zB)
+{
+    static_assert(MODE == 0 || MODE == 1, "raw or clamped fetch only");
+    constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;
+    constexpr int TM = 4, TN = 2;
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int NQ = BN / 4;
+    constexpr int B_PLANE = NQ * 16 + 64;
+    constexpr int B_BLOCK = 4 * B_PLANE;
+    constexpr int A_BYTES = BM * A_STRIDE, B_BYTES = 4 * B_BLOCK;
+    constexpr int A_PT = BM * 4 / 128;  // uint4 loads of A per A-loader thread (128 of them)
+    static_assert(4 * NQ == 128, "one B unit per B-loader thread");
+
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2][A_BYTES + B_BYTES];
+    __shared__ int32_t sums[U8 ? (BM + BN) * 4 : 1];  // rsum[row][4 depth quarters], csum[column][4 depth blocks]
+
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nMB * nNB)
+        return;
+    const int nb = idx / nMB, mb = idx - nb * nMB;
+    const int m0 = mb * BM, n0 = nb * BN;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nsteps = (K + BK - 1) / BK;
+    int32_t *rsum = sums, *csum = sums + (U8 ? BM * 4 : 0);
+
+    if (wave >= 6) {
+        // ------------------------------------------------------------------ A loaders
+        const int t = tid - 384;  // 0..127
+        uint4 pre[DEPTH][A_PT];
+        uint32_t rs_acc[A_PT];  // unsigned byte sums, 16 bytes per step each (see the 4-wave kernel)
+#pragma unroll
+        for (int p = 0; p < A_PT; ++p)
+            rs_acc[p] = 0;
+        // loads of a step beyond the last one re-read the last step (never used): no load sits under a branch
+        auto load = [&](uint4(&dst)[A_PT], int step) __attribute__((always_inline)) {
+            const int k0 = (step < nsteps ? step : nsteps - 1) * BK;
+#pragma unroll
+            for (int p = 0; p < A_PT; ++p) {
+                const int u = t + p * 128;
+                const int r = m0 + (u >> 2), k = k0 + (u & 3) * 16;
+                if constexpr (MODE == 0) {
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)r * lda + k);
+                    dst[p] = make_uint4(src[0], src[1], src[2], src[3]);
+                } else {
+                    const bool ok = r < M && k + 16 <= K;
+                    const int rr = r < M ? r : M - 1, kk = k + 16 <= K ? k : K - 16;
+                    const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)rr * lda + kk);
+                    dst[p] = make_uint4(ok ? src[0] : FLIP, ok ? src[1] : FLIP, ok ? src[2] : FLIP, ok ? src[3] : FLIP);
+                }
+            }
+        };
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            load(pre[d], d);
+        auto commit = [&](const uint4(&src)[A_PT], int buf) __attribute__((always_inline)) {
+            uint8_t *As = smem[buf];
+#pragma unroll
+            for (int p = 0; p < A_PT; ++p) {
+                const int u = t + p * 128;
+                const uint4 v = src[p];
+                *reinterpret_cast<uint4 *>(&As[(u >> 2) * A_STRIDE + (u & 3) * 16]) =
+                    make_uint4(v.x ^ FLIP, v.y ^ FLIP, v.z ^ FLIP, v.w ^ FLIP);
+                if constexpr (U8)
+                    rs_acc[p] = bytesum(v.x, bytesum(v.y, bytesum(v.z, bytesum(v.w, rs_acc[p]))));
+            }
+        };
+        // Groups of DEPTH steps with compile-time slot numbers and no branch inside, so that the compiler's count of
+        // loads that may stay in flight at each use is exact; the last nsteps % DEPTH steps need no further loads.
+        const int full = nsteps / DEPTH * DEPTH;
+        int s0 = 0;
+        for (; s0 < full; s0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                commit(pre[d], (s0 + d) & 1);
+                load(pre[d], s0 + d + DEPTH);
+                lds_barrier();
+            }
+        }
+#pragma unroll
+        for (int d = 0; d + 1 < DEPTH; ++d)
+            if (s0 + d < nsteps) {
+                commit(pre[d], (s0 + d) & 1);
+                lds_barrier();
+            }
+        if constexpr (U8) {
+#pragma unroll
+            for (int p = 0; p < A_PT; ++p)
+                rsum[t + p * 128] = (int32_t)rs_acc[p] - 2048 * nsteps;  // unit u = row*4 + quarter
+            lds_barrier();
+        }
+        return;
+    }
+    if (wave >= 4) {
+        // ------------------------------------------------------------------ B loaders
+        const int u = tid - 256;  // 0..127: one (depth block of 16, column quad) unit
+        const int kb = u / NQ, nq = u % NQ;
+        uint32_t pre[DEPTH][16];
+        uint32_t cs_acc[4] = {0u, 0u, 0u, 0u};
+        auto load = [&](uint32_t(&dst)[16], int step) __attribute__((always_inline)) {
+            const int k0 = (step < nsteps ? step : nsteps - 1) * BK + kb * 16;
+            const int n = n0 + nq * 4;
+            if constexpr (MODE == 0) {
+                const int8_t *src = B + (int64_t)k0 * ldb + n;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    dst[j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb);
+            } else {
+                const int nn = n + 4 <= N ? n : N - 4;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int k = k0 + j;
+                    const int kk = k < K ? k : K - 1;
+                    const uint32_t x = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
+                    dst[j] = (k < K && n + 4 <= N) ? x : FLIP;
+                }
+            }
+        };
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            load(pre[d], d);
+        auto commit = [&](const uint32_t(&src)[16], int buf) __attribute__((always_inline)) {
+            uint8_t *Bs = smem[buf] + A_BYTES;
+            uint32_t o[4][4];  // o[q][i]: depth quad q, column i
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                transpose4x4(&src[q * 4], o[q]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                *reinterpret_cast<uint4 *>(&Bs[kb * B_BLOCK + i * B_PLANE + nq * 16]) =
+                    make_uint4(o[0][i] ^ FLIP, o[1][i] ^ FLIP, o[2][i] ^ FLIP, o[3][i] ^ FLIP);
+                if constexpr (U8)
+                    cs_acc[i] = bytesum(o[0][i], bytesum(o[1][i], bytesum(o[2][i], bytesum(o[3][i], cs_acc[i]))));
+            }
+        };
+        const int full = nsteps / DEPTH * DEPTH;
+        int s0 = 0;
+        for (; s0 < full; s0 += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                commit(pre[d], (s0 + d) & 1);
+                load(pre[d], s0 + d + DEPTH);
+                lds_barrier();
+            }
+        }
+#pragma unroll
+        for (int d = 0; d + 1 < DEPTH; ++d)
+            if (s0 + d < nsteps) {
+                commit(pre[d], (s0 + d) & 1);
+                lds_barrier();
+            }
+        if constexpr (U8) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                csum[(nq * 4 + i) * 4 + kb] = (int32_t)cs_acc[i] - 2048 * nsteps;
+            lds_barrier();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int wm = wave & 1, wn = wave >> 1;
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0;
+
+    auto read_frags = [&](int buf, int ks, v4i(&af)[TM], v4i(&bf)[TN]) __attribute__((always_inline)) {
+        const uint8_t *As = smem[buf], *Bs = smem[buf] + A_BYTES;
+        const int kb = ks * 2 + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = (wm * TM + i) * 32 + (lane & 31);
+            af[i] = *reinterpret_cast<const v4i *>(&As[row * A_STRIDE + kb * 16]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = (wn * TN + j) * 32 + (lane & 31);
+            bf[j] = *reinterpret_cast<const v4i *>(&Bs[kb * B_BLOCK + (col & 3) * B_PLANE + (col >> 2) * 16]);
+        }
+    };
+    auto mfma_all = [&](const v4i(&af)[TM], const v4i(&bf)[TN]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+    };
+
+    v4i fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    lds_barrier();  // barrier 0
+    read_frags(0, 0, fa0, fb0);
+    // The scheduling fences pin "issue the fragment reads of the next half step, then the 8 MFMAs of this one":
+    // left alone, the scheduler sinks the reads below the MFMAs to reuse the fragment registers, and the LDS
+    // latency is then exposed twice per step.
+    for (int s = 0; s + 1 < nsteps; ++s) {
+        read_frags(s & 1, 1, fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_all(fa0, fb0);
+        lds_barrier();  // barrier s+1; every read of buffer s%2 has completed
+        read_frags((s + 1) & 1, 0, fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_all(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    read_frags((nsteps - 1) & 1, 1, fa1, fb1);  // last step, peeled so that the loop body has no branch
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_all(fa0, fb0);
+    mfma_all(fa1, fb1);
+    if constexpr (U8)
+        lds_barrier();  // the sums are in LDS
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int lcol = (wn * TN + j) * 32 + (lane & 31);
+            const int col = n0 + lcol;
+            int32_t ccorr = 0;
+            if constexpr (U8)
+                ccorr = K * zA * zB - zA * (csum[lcol * 4] + csum[lcol * 4 + 1] + csum[lcol * 4 + 2] + csum[lcol * 4 + 3]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lrow = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int row = m0 + lrow;
+                int32_t out = acc[i][j][r];
+                if constexpr (U8)
+                    out += ccorr - zB * (rsum[lrow * 4] + rsum[lrow * 4 + 1] + rsum[lrow * 4 + 2] + rsum[lrow * 4 + 3]);
+                if (MODE == 0 || (row < M && col < N))
                     C[(int64_t)row * ldc + col] = out;
             }
         }
@@ -334,6 +611,35 @@ hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t
     return hipGetLastError();
 }
 
+// Wave-specialised 256 x 128 instance; returns hipErrorNotSupported when the operands are not aligned or the shape
+// needs byte-wise fetches (the caller then falls back to the 4-wave kernel).
+template <bool U8, int DEPTH>
+hipError_t launch_ws(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                     int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
+{
+    constexpr int BM = 256, BN = 128;
+    const int nMB = (int)((M + BM - 1) / BM), nNB = (int)((N + BN - 1) / BN);
+    const int64_t tiles = (int64_t)nMB * nNB;
+    const int tiles_per_xcd = (int)((tiles + 7) / 8);
+    const int64_t grid = (int64_t)tiles_per_xcd * 8;
+    if (grid > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(B) % 4 == 0) && (ldb % 4 == 0);
+    const bool whole = (M % BM) == 0 && (N % BN) == 0 && (K % BK) == 0;
+    const bool can_clamp = (N % 4) == 0 && (K % 16) == 0 && N >= 4 && K >= 16;
+    const dim3 g((unsigned)grid), b(512);
+    if (aligned && whole)
+        hipLaunchKernelGGL((gemm_i8_ws_kernel<0, U8, DEPTH>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B, ldb, C,
+                           ldc, nMB, nNB, tiles_per_xcd, zA, zB);
+    else if (aligned && can_clamp)
+        hipLaunchKernelGGL((gemm_i8_ws_kernel<1, U8, DEPTH>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B, ldb, C,
+                           ldc, nMB, nNB, tiles_per_xcd, zA, zB);
+    else
+        return hipErrorNotSupported;
+    return hipGetLastError();
+}
+
 int g_i8_forced = -1;
 
 }  // namespace
@@ -350,7 +656,15 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     if (t < 0 && N <= 16 && M >= 64)
         return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
     if (t < 0)
-        t = big_tiles >= 512 ? 2 : 0;
+        t = big_tiles >= 512 ? 3 : 0;
+    if (t >= 3) {
+        const hipError_t e = t == 3   ? launch_ws<false, 3>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                             : t == 4 ? launch_ws<false, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                                      : launch_ws<false, 4>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+        if (e != hipErrorNotSupported)
+            return e;
+        t = 2;
+    }
     if (t == 1)
         return launch_tile<4, 4, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     if (t == 2)
@@ -364,8 +678,12 @@ hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int
 {
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     const int8_t *a = reinterpret_cast<const int8_t *>(A), *b = reinterpret_cast<const int8_t *>(B);
-    if (big_tiles >= 512)
+    if (big_tiles >= 512) {
+        const hipError_t e = launch_ws<true, 3>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+        if (e != hipErrorNotSupported)
+            return e;
         return launch_tile<4, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+    }
     return launch_tile<2, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
 }
 

@@ -225,7 +225,9 @@ def test_deterministic():
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (128, 128, 64), (257, 300, 1000),
                                    (512, 784, 2304), (33, 8, 4096), (300, 515, 131), (256, 256, 64),
-                                   (4096, 8, 2048), (100, 5, 3000), (64, 16, 4100), (257, 9, 16), (1000, 8, 8192)])
+                                   (4096, 8, 2048), (100, 5, 3000), (64, 16, 4100), (257, 9, 16), (1000, 8, 8192),
+                                   (256, 128, 64), (512, 256, 128), (256, 384, 192), (512, 128, 448), (300, 516, 144),
+                                   (20, 24, 16), (700, 260, 1040)])
 def test_i8_mfma(M, N, K):
     say(f"gemm_i8_mfma M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
@@ -233,13 +235,29 @@ def test_i8_mfma(M, N, K):
     B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
     want = oracle.gemm(A, B)
     try:
-        for tile in (-1, 0, 1, 2):
+        for tile in range(-1, lb.lb_num_variants(4)):  # 4-wave tiles and the wave-specialised instances
             lb.lb_set_variant(4, tile)
             got = lb.gemm_i8_mfma(M, N, K, dev(A), K, dev(B), N)
             torch.cuda.synchronize()
             assert np.array_equal(got.cpu().numpy(), want), tile
     finally:
         lb.lb_set_variant(4, -1)
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 16384, 192), (2048, 16512, 208), (2300, 16384, 64)])
+def test_i8_and_u8_large_default_path(M, N, K):
+    """Shapes large enough for the shape-based choice to take the wave-specialised kernel (whole and ragged tiles)."""
+    say(f"gemm_i8_mfma / gemm_u8_mfma default path M={M} N={N} K={K}")
+    rng = np.random.default_rng(M + N + K)
+    A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+    B = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+    got = lb.gemm_i8_mfma(M, N, K, dev(A), K, dev(B), N)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.gemm(A, B))
+    Au, Bu = A.view(np.uint8), B.view(np.uint8)
+    got = lb.gemm_u8_mfma(M, N, K, dev(Au), K, dev(Bu), N, 3, 250)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), oracle.gemm_u8_zero_point(Au, Bu, 3, 250))
 
 
 def test_i8_mfma_on_ternary_config():
