@@ -555,7 +555,7 @@ int lb_set_variant(int op, int variant)
 {
     int count = 0;
     if (op == 4) {
-        if (variant < -1 || variant > 5)
+        if (variant < -1 || variant > 11)
             return fail(LB_EINVAL, "lb_set_variant: int8 tile %d out of range", variant);
         lowbit::i8_force_tile(variant);
         return LB_OK;
@@ -580,7 +580,7 @@ int lb_num_variants(int op)
     if (op == 3)
         return lowbit::skinny_num_configs();
     if (op == 4)
-        return 6;
+        return 8;
     if (op < 0 || op > 2)
         return 0;
     lowbit::gemm_variants(op, &count);

@@ -35,6 +35,7 @@
 namespace lowbit {
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -583,6 +584,213 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
         }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Direct-to-LDS instance for large, aligned, whole-tile problems: 256 x 128 tile, 8 waves.
+//
+// In the kernels above every operand byte crosses the register file twice (global -> VGPR -> LDS -> VGPR), and the
+// returns of the global loads and of the LDS fragment reads share the way into the registers: measured on the
+// wave-specialised kernel, global loads alone or fragment reads alone take half the time the two take together.
+// Here global memory is read straight into LDS (global_load_lds_dwordx4: lane l of a wave-wide load writes 16 bytes
+// at LDS base + 16*l), so only fragments enter registers:
+//   A tile  [row][BKB depth bytes]; the 16-byte chunk c of a row is stored at slot c ^ f(row), f chosen so that the
+//           ds_read_b128 of an MFMA A fragment (32 consecutive rows, one chunk) spreads over all banks.  With
+//           BKB = 128 a row of the tile is one whole 128-byte cache line of A; half lines (BKB = 64) move through
+//           the caches at about half the rate, which is why the 128-byte stage is the default.
+//   B tile  [depth row][128 column bytes] as in memory (no transpose on the way in), chunk c of depth row r stored
+//           at slot c ^ (r & 7).  The MFMA B fragment (16 depth bytes of one column per lane) is read with the
+//           transposing LDS read ds_read_b64_tr_b8: 16 lanes hand in the addresses of 8 rows x 16 bytes (lanes 2m and
+//           2m+1 the two halves of row m) and lane i receives byte i of each of the 8 rows.
+// The swizzles cost nothing: a lane of a direct load may fetch any global chunk, only its LDS slot is fixed.
+// Waves 0-3 multiply as in the wave-specialised kernel; waves 4-7 issue the direct loads (no data registers),
+// STAGES - 1 depth stages ahead through a ring of STAGES LDS stages.  Barrier k means "stage k % STAGES holds depth
+// step k"; a loader waits for its own loads of step k (vmcnt) before barrier k and refills the stage of step k - 1
+// after it, which every consumer has finished reading by then.
+template <int STAGES, int BKB>
+__global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__restrict__ A, int64_t lda,
+                                                         const int8_t *__restrict__ B, int64_t ldb,
+                                                         int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB,
+                                                         int tiles_per_xcd)
+{
+    constexpr int TM = 4, TN = 2;
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int KS = BKB / 32;                          // MFMA depth steps per stage
+    constexpr int CA = BKB / 16;                          // 16-byte chunks per A row
+    constexpr int RA = 64 / CA;                           // A rows per wave-wide load
+    constexpr int SH = CA == 4 ? 2 : 1;                   // A slot swizzle: chunk ^ ((row >> SH) & (CA - 1))
+    constexpr int A_BYTES = BM * BKB, B_BYTES = BKB * BN;
+    constexpr int STAGE = A_BYTES + B_BYTES;
+    constexpr int A_LOADS = A_BYTES / 1024 / 4, B_LOADS = B_BYTES / 1024 / 4;  // per loader wave and step
+    constexpr int LOADS = A_LOADS + B_LOADS;
+    static_assert(BN == 128 && (BKB == 64 || BKB == 128), "slot arithmetic below assumes 8 chunks per B row");
+
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[STAGES * STAGE];
+
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nMB * nNB)
+        return;
+    const int nb = idx / nMB, mb = idx - nb * nMB;
+    const int m0 = mb * BM, n0 = nb * BN;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int nsteps = K / BKB;
+
+    if (wave >= 4) {
+        // ------------------------------------------------------------------ loaders
+        const int w = wave - 4;
+        // A: wave-wide load q covers rows RA*q .. RA*q+RA-1; this wave issues q = A_LOADS*w .. A_LOADS*w + A_LOADS-1.
+        // With 8 chunks per row the swizzle term (row >> 1) & 7 has a bit that alternates with q.
+        const int a_row = lane / CA, a_slot = lane % CA;
+        const int a_chunk0 = a_slot ^ ((a_row >> SH) & (CA - 1));
+        const int a_chunk1 = CA == 8 ? (a_chunk0 ^ 4) : a_chunk0;            // odd q when RA = 8
+        const int8_t *a_base = A + (int64_t)(m0 + RA * A_LOADS * w + a_row) * lda;
+        // B: wave-wide load q covers depth rows 8q .. 8q+7; this wave issues q = B_LOADS*w .. B_LOADS*w + B_LOADS-1
+        const int b_row = lane >> 3;
+        const int b_chunk = (lane & 7) ^ b_row;
+        const int8_t *b_base = B + (int64_t)(8 * B_LOADS * w + b_row) * ldb + n0 + b_chunk * 16;
+        auto issue = [&](int step) __attribute__((always_inline)) {
+            uint8_t *st = smem + (step % STAGES) * STAGE;
+            const int8_t *pa = a_base + (int64_t)step * BKB;
+            const int8_t *pb = b_base + (int64_t)step * BKB * ldb;
+#pragma unroll
+            for (int q = 0; q < A_LOADS; ++q)
+                __builtin_amdgcn_global_load_lds(
+                    (const void __attribute__((address_space(1))) *)(pa + (int64_t)(RA * q) * lda + ((q & 1) ? a_chunk1 : a_chunk0) * 16),
+                    (void __attribute__((address_space(3))) *)(st + (A_LOADS * w + q) * 1024), 16, 0, 0);
+#pragma unroll
+            for (int q = 0; q < B_LOADS; ++q)
+                __builtin_amdgcn_global_load_lds(
+                    (const void __attribute__((address_space(1))) *)(pb + (int64_t)(8 * q) * ldb),
+                    (void __attribute__((address_space(3))) *)(st + A_BYTES + (B_LOADS * w + q) * 1024), 16, 0, 0);
+        };
+        constexpr int AHEAD = STAGES - 1;
+        for (int s = 0; s < AHEAD && s < nsteps; ++s)
+            issue(s);
+        int s = 0;
+        for (; s + AHEAD < nsteps; ++s) {
+            // the loads of steps s+1 .. s+AHEAD-1 may stay in flight; those of step s must have landed
+            constexpr int vm = (AHEAD - 1) * LOADS;
+            static_assert(vm < 64, "vmcnt is a 6-bit counter");
+            __builtin_amdgcn_s_waitcnt((vm & 15) | ((vm >> 4) << 14) | 0x0f70);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            issue(s + AHEAD);
+        }
+        for (; s < nsteps; ++s) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): no further loads are issued
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int wm = wave & 1, wn = wave >> 1;
+    v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0;
+
+    // fragment addresses inside a stage for depth step ks = 0; the others follow by XOR / addition below
+    const int l32 = lane & 31, khalf = lane >> 5;
+    int a_row_off[TM], a_swz[TM], b_off[TN][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = (wm * TM + i) * 32 + l32;
+        a_row_off[i] = row * BKB;
+        a_swz[i] = (row >> SH) & (CA - 1);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int chunk = (wn * TN + j) * 2 + (l32 >> 4);  // 16-column chunk of the tile row
+        const int jj = lane & 15;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int row = 16 * khalf + 8 * r + (jj >> 1);  // + 32*ks: leaves row & 7 unchanged
+            b_off[j][r] = A_BYTES + row * BN + ((chunk ^ (row & 7)) << 4) + 8 * (jj & 1);
+        }
+    }
+    auto read_frags = [&](int stage, int ks, v4i(&af)[TM], v4i(&bf)[TN]) __attribute__((always_inline)) {
+        const uint8_t *st = smem + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            af[i] = *reinterpret_cast<const v4i *>(st + a_row_off[i] + (((2 * ks + khalf) ^ a_swz[i]) << 4));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                (v2i __attribute__((address_space(3))) *)(st + b_off[j][0] + ks * 32 * BN));
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                (v2i __attribute__((address_space(3))) *)(st + b_off[j][1] + ks * 32 * BN));
+            bf[j] = v4i{lo[0], lo[1], hi[0], hi[1]};
+        }
+    };
+    auto mfma_rows = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int i0, int i1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+    };
+
+    // Per MFMA depth step: the first two MFMAs, then the fragment reads of the next depth step, then the other six.
+    // The compiler waits for ALL outstanding LDS reads before the first use of a fragment, so the reads of the next
+    // depth step are issued only after the current fragments have been touched; six MFMAs (192 cycles) cover their
+    // latency.  Two fragment sets alternate; the barrier sits in front of the last depth step of a stage, whose
+    // fragments are in registers by then, so that the first fragments of the next stage can be read behind it.
+    v4i fa[2][TM], fb[2][TN];
+    lds_barrier();  // barrier 0
+    read_frags(0, 0, fa[0], fb[0]);
+    int stage = 0;
+    for (int s = 0; s + 1 < nsteps; ++s) {
+        const int next = stage + 1 == STAGES ? 0 : stage + 1;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1;
+            if (ks == KS - 1)
+                lds_barrier();  // barrier s+1; every read of step s has completed
+            mfma_rows(fa[cur], fb[cur], 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == KS - 1)
+                read_frags(next, 0, fa[cur ^ 1], fb[cur ^ 1]);
+            else
+                read_frags(stage, ks + 1, fa[cur ^ 1], fb[cur ^ 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_rows(fa[cur], fb[cur], 1, TM);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage = next;
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {  // last stage: nothing follows it
+        const int cur = ks & 1;
+        mfma_rows(fa[cur], fb[cur], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + 1 < KS)
+            read_frags(stage, ks + 1, fa[cur ^ 1], fb[cur ^ 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_rows(fa[cur], fb[cur], 1, TM);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                C[(int64_t)row * ldc + col] = acc[i][j][r];
+            }
+        }
+}
+
 template <int TM, int TN, bool U8>
 hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                        int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
@@ -640,6 +848,28 @@ hipError_t launch_ws(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t l
     return hipGetLastError();
 }
 
+// Direct-to-LDS 256 x 128 instance; hipErrorNotSupported unless the tiles are whole and every 16-byte chunk aligned.
+template <int STAGES, int BKB>
+hipError_t launch_dl(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                     int32_t *C, int64_t ldc, hipStream_t stream)
+{
+    constexpr int BM = 256, BN = 128;
+    const bool ok = (M % BM) == 0 && (N % BN) == 0 && (K % BKB) == 0 && K >= BKB &&
+                    (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
+                    (reinterpret_cast<uintptr_t>(B) % 16 == 0) && (ldb % 16 == 0);
+    if (!ok)
+        return hipErrorNotSupported;
+    const int nMB = (int)(M / BM), nNB = (int)(N / BN);
+    const int64_t tiles = (int64_t)nMB * nNB;
+    const int tiles_per_xcd = (int)((tiles + 7) / 8);
+    const int64_t grid = (int64_t)tiles_per_xcd * 8;
+    if (grid > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((gemm_i8_dl_kernel<STAGES, BKB>), dim3((unsigned)grid), dim3(512), 0, stream, (int)K, A, lda, B, ldb, C,
+                       ldc, nMB, nNB, tiles_per_xcd);
+    return hipGetLastError();
+}
+
 int g_i8_forced = -1;
 
 }  // namespace
@@ -656,7 +886,14 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     if (t < 0 && N <= 16 && M >= 64)
         return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
     if (t < 0)
-        t = big_tiles >= 512 ? 3 : 0;
+        t = big_tiles >= 512 ? 7 : 0;
+    if (t >= 6) {
+        const hipError_t e = t == 6 ? launch_dl<4, 64>(M, N, K, A, lda, B, ldb, C, ldc, stream)
+                                    : launch_dl<3, 128>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+        if (e != hipErrorNotSupported)
+            return e;
+        t = 3;
+    }
     if (t >= 3) {
         const hipError_t e = t == 3   ? launch_ws<false, 3>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
                              : t == 4 ? launch_ws<false, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)

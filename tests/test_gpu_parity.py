@@ -227,7 +227,8 @@ def test_deterministic():
                                    (512, 784, 2304), (33, 8, 4096), (300, 515, 131), (256, 256, 64),
                                    (4096, 8, 2048), (100, 5, 3000), (64, 16, 4100), (257, 9, 16), (1000, 8, 8192),
                                    (256, 128, 64), (512, 256, 128), (256, 384, 192), (512, 128, 448), (300, 516, 144),
-                                   (20, 24, 16), (700, 260, 1040)])
+                                   (20, 24, 16), (700, 260, 1040), (256, 256, 128), (512, 512, 384),
+                                   (256, 768, 1280), (768, 256, 256)])
 def test_i8_mfma(M, N, K):
     say(f"gemm_i8_mfma M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
@@ -244,9 +245,10 @@ def test_i8_mfma(M, N, K):
         lb.lb_set_variant(4, -1)
 
 
-@pytest.mark.parametrize("M,N,K", [(2048, 16384, 192), (2048, 16512, 208), (2300, 16384, 64)])
+@pytest.mark.parametrize("M,N,K", [(2048, 16384, 192), (2048, 16512, 208), (2300, 16384, 64), (2048, 16384, 384)])
 def test_i8_and_u8_large_default_path(M, N, K):
-    """Shapes large enough for the shape-based choice to take the wave-specialised kernel (whole and ragged tiles)."""
+    """Shapes large enough for the shape-based choice to take the direct-to-LDS kernel (whole tiles, depth a multiple
+    of 128) or the wave-specialised one (everything else, ragged tiles included)."""
     say(f"gemm_i8_mfma / gemm_u8_mfma default path M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
     A = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
