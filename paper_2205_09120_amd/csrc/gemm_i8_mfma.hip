@@ -30,6 +30,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "lowbit_internal.h"
 
 namespace lowbit {
@@ -604,13 +606,15 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 // Waves 0-3 multiply as in the wave-specialised kernel; waves 4-7 issue the direct loads (no data registers),
 // STAGES - 1 depth stages ahead through a ring of STAGES LDS stages.  Barrier k means "stage k % STAGES holds depth
 // step k"; a loader waits for its own loads of step k (vmcnt) before barrier k and refills the stage of step k - 1
-// after it, which every consumer has finished reading by then.
-template <int STAGES, int BKB>
+// after it, which every consumer has finished reading by then.  Unsigned operands (U8): the bytes cannot be re-biased
+// on the way in, so the consumers do it on the fragments and also take the byte sums of eq. (3) from them.
+template <int STAGES, int BKB, bool U8>
 __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__restrict__ A, int64_t lda,
                                                          const int8_t *__restrict__ B, int64_t ldb,
                                                          int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB,
-                                                         int tiles_per_xcd)
+                                                         int tiles_per_xcd, int zA, int zB)
 {
+    constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;  // unsigned byte -> signed byte minus 128
     constexpr int TM = 4, TN = 2;
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int KS = BKB / 32;                          // MFMA depth steps per stage
@@ -624,6 +628,7 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
     static_assert(BN == 128 && (BKB == 64 || BKB == 128), "slot arithmetic below assumes 8 chunks per B row");
 
     __shared__ __attribute__((aligned(1024))) uint8_t smem[STAGES * STAGE];
+    __shared__ uint32_t sums[U8 ? (BM + BN) * 2 : 1];  // U8: unsigned byte sums, [row or column][depth half of the lane]
 
     const int bid = blockIdx.x;
     const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
@@ -683,6 +688,8 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
             asm volatile("s_barrier" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (U8)
+            asm volatile("s_barrier" ::: "memory");  // matches the consumers' barrier behind their byte sums
         return;
     }
 
@@ -730,12 +737,40 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
             bf[j] = v4i{lo[0], lo[1], hi[0], hi[1]};
         }
     };
-    auto mfma_rows = [&](const v4i(&af)[TM], const v4i(&bf)[TN], int i0, int i1) __attribute__((always_inline)) {
+    // Unsigned operands: the fragments hold raw bytes.  Each is re-biased (XOR) right before its first MFMA, and one
+    // wave per row block / column block adds the raw bytes up (v_sad_u8 against zero) for the corrections of eq. (3):
+    // waves (0,0) and (1,1) sum the A rows of their row block, waves (1,0) and (0,1) the B columns of their column
+    // block.  The main loop is instantiated once per role (no per-instruction selects), and the preparation of row
+    // i+1 issues behind the MFMAs of row i.
+    const bool sum_a = U8 && wm == wn, sum_b = U8 && wm != wn;
+    uint32_t rs[TM] = {0u, 0u, 0u, 0u}, cs[TN] = {0u, 0u};
+    auto flip = [&](v4i &f) __attribute__((always_inline)) {
+        f = v4i{(int)((uint32_t)f[0] ^ FLIP), (int)((uint32_t)f[1] ^ FLIP), (int)((uint32_t)f[2] ^ FLIP), (int)((uint32_t)f[3] ^ FLIP)};
+    };
+    auto add_bytes = [&](const v4i &f, uint32_t &t) __attribute__((always_inline)) {
+        t = bytesum((uint32_t)f[0], bytesum((uint32_t)f[1], bytesum((uint32_t)f[2], bytesum((uint32_t)f[3], t))));
+    };
+    // rows i0 .. i1-1 of the wave's 4 x 2 MFMA tiles; the B fragments are prepared with row 0
+    auto mfma_rows = [&](auto sa, auto sb, v4i(&af)[TM], v4i(&bf)[TN], int i0, int i1) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = i0; i < i1; ++i)
+        for (int i = i0; i < i1; ++i) {
+            if constexpr (U8) {
+                if (i == 0) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if constexpr (decltype(sb)::value)
+                            add_bytes(bf[j], cs[j]);
+                        flip(bf[j]);
+                    }
+                }
+                if constexpr (decltype(sa)::value)
+                    add_bytes(af[i], rs[i]);
+                flip(af[i]);
+            }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
     };
 
     // Per MFMA depth step: the first two MFMAs, then the fragment reads of the next depth step, then the other six.
@@ -743,50 +778,82 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
     // depth step are issued only after the current fragments have been touched; six MFMAs (192 cycles) cover their
     // latency.  Two fragment sets alternate; the barrier sits in front of the last depth step of a stage, whose
     // fragments are in registers by then, so that the first fragments of the next stage can be read behind it.
-    v4i fa[2][TM], fb[2][TN];
-    lds_barrier();  // barrier 0
-    read_frags(0, 0, fa[0], fb[0]);
-    int stage = 0;
-    for (int s = 0; s + 1 < nsteps; ++s) {
-        const int next = stage + 1 == STAGES ? 0 : stage + 1;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
+    auto main_loop = [&](auto sa, auto sb) __attribute__((always_inline)) {
+        v4i fa[2][TM], fb[2][TN];
+        lds_barrier();  // barrier 0
+        read_frags(0, 0, fa[0], fb[0]);
+        int stage = 0;
+        for (int s = 0; s + 1 < nsteps; ++s) {
+            const int next = stage + 1 == STAGES ? 0 : stage + 1;
+    #pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cur = ks & 1;
+                if (ks == KS - 1)
+                    lds_barrier();  // barrier s+1; every read of step s has completed
+                mfma_rows(sa, sb, fa[cur], fb[cur], 0, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks == KS - 1)
+                    read_frags(next, 0, fa[cur ^ 1], fb[cur ^ 1]);
+                else
+                    read_frags(stage, ks + 1, fa[cur ^ 1], fb[cur ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_rows(sa, sb, fa[cur], fb[cur], 1, TM);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage = next;
+        }
+    #pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {  // last stage: nothing follows it
             const int cur = ks & 1;
-            if (ks == KS - 1)
-                lds_barrier();  // barrier s+1; every read of step s has completed
-            mfma_rows(fa[cur], fb[cur], 0, 1);
+            mfma_rows(sa, sb, fa[cur], fb[cur], 0, 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (ks == KS - 1)
-                read_frags(next, 0, fa[cur ^ 1], fb[cur ^ 1]);
-            else
+            if (ks + 1 < KS)
                 read_frags(stage, ks + 1, fa[cur ^ 1], fb[cur ^ 1]);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_rows(fa[cur], fb[cur], 1, TM);
+            mfma_rows(sa, sb, fa[cur], fb[cur], 1, TM);
             __builtin_amdgcn_sched_barrier(0);
         }
-        stage = next;
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {  // last stage: nothing follows it
-        const int cur = ks & 1;
-        mfma_rows(fa[cur], fb[cur], 0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks + 1 < KS)
-            read_frags(stage, ks + 1, fa[cur ^ 1], fb[cur ^ 1]);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_rows(fa[cur], fb[cur], 1, TM);
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    };
+    using std::false_type;
+    using std::true_type;
+    if (sum_a)
+        main_loop(true_type{}, false_type{});
+    else if (sum_b)
+        main_loop(false_type{}, true_type{});
+    else
+        main_loop(false_type{}, false_type{});
 
+    // U8: sums -> LDS, [index][depth half]; every row / column block has exactly one summing wave
+    uint32_t *rsum = sums, *csum = sums + (U8 ? BM * 2 : 0);
+    if constexpr (U8) {
+        if (sum_a) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                rsum[((wm * TM + i) * 32 + l32) * 2 + khalf] = rs[i];
+        }
+        if (sum_b) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                csum[((wn * TN + j) * 32 + l32) * 2 + khalf] = cs[j];
+        }
+        lds_barrier();
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = n0 + (wn * TN + j) * 32 + (lane & 31);
+            const int lcol = (wn * TN + j) * 32 + (lane & 31);
+            const int col = n0 + lcol;
+            int32_t ccorr = 0;
+            if constexpr (U8)  // signed sums = unsigned sums - 128 per byte; all K bytes are real (whole tiles)
+                ccorr = K * zA * zB - zA * ((int32_t)(csum[lcol * 2] + csum[lcol * 2 + 1]) - 128 * K);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                C[(int64_t)row * ldc + col] = acc[i][j][r];
+                const int lrow = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                int32_t out = acc[i][j][r];
+                if constexpr (U8)
+                    out += ccorr - zB * ((int32_t)(rsum[lrow * 2] + rsum[lrow * 2 + 1]) - 128 * K);
+                C[(int64_t)(m0 + lrow) * ldc + col] = out;
             }
         }
 }
@@ -849,9 +916,9 @@ hipError_t launch_ws(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t l
 }
 
 // Direct-to-LDS 256 x 128 instance; hipErrorNotSupported unless the tiles are whole and every 16-byte chunk aligned.
-template <int STAGES, int BKB>
+template <int STAGES, int BKB, bool U8>
 hipError_t launch_dl(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
-                     int32_t *C, int64_t ldc, hipStream_t stream)
+                     int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
 {
     constexpr int BM = 256, BN = 128;
     const bool ok = (M % BM) == 0 && (N % BN) == 0 && (K % BKB) == 0 && K >= BKB &&
@@ -865,8 +932,8 @@ hipError_t launch_dl(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t l
     const int64_t grid = (int64_t)tiles_per_xcd * 8;
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_i8_dl_kernel<STAGES, BKB>), dim3((unsigned)grid), dim3(512), 0, stream, (int)K, A, lda, B, ldb, C,
-                       ldc, nMB, nNB, tiles_per_xcd);
+    hipLaunchKernelGGL((gemm_i8_dl_kernel<STAGES, BKB, U8>), dim3((unsigned)grid), dim3(512), 0, stream, (int)K, A, lda, B,
+                       ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     return hipGetLastError();
 }
 
@@ -888,8 +955,8 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     if (t < 0)
         t = big_tiles >= 512 ? 7 : 0;
     if (t >= 6) {
-        const hipError_t e = t == 6 ? launch_dl<4, 64>(M, N, K, A, lda, B, ldb, C, ldc, stream)
-                                    : launch_dl<3, 128>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+        const hipError_t e = t == 6 ? launch_dl<4, 64, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                                    : launch_dl<3, 128, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
         if (e != hipErrorNotSupported)
             return e;
         t = 3;
@@ -916,7 +983,10 @@ hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
     const int8_t *a = reinterpret_cast<const int8_t *>(A), *b = reinterpret_cast<const int8_t *>(B);
     if (big_tiles >= 512) {
-        const hipError_t e = launch_ws<true, 3>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+        hipError_t e = launch_dl<3, 128, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+        if (e != hipErrorNotSupported)
+            return e;
+        e = launch_ws<true, 3>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
         if (e != hipErrorNotSupported)
             return e;
         return launch_tile<4, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
