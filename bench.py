@@ -369,6 +369,10 @@ def main() -> int:
                 it = iter(range(10 ** 9))
                 cold = graph_time(lambda: lb.gemm(ww.kind, ww.M, ww.N, ww.K, copies[next(it) % ncopy], bp_, c_, ww.N),
                                   ncopy, 5)
+                # the floor for one launch at this size: a kernel that only reads the same cold bytes
+                nbytes = copies[0].numel() * 8
+                floor = graph_time(lambda: lb.lb_calib_stream(0, copies[next(it) % ncopy], None, nbytes, sink),
+                                   ncopy, 5)
                 del copies
             others[name] = {"gemm_us": t * 1e6, "tops": ww.ops / t / 1e12, "int8_mfma_us": t8 * 1e6,
                             "speedup_vs_int8_mfma": t8 / t,
@@ -377,6 +381,7 @@ def main() -> int:
             if cold is not None:
                 others[name]["gemm_us_cold_operand"] = cold * 1e6
                 others[name]["hbm_frac_cold_operand"] = packed_bytes / cold / 1e9 / HBM_PEAK_GBS
+                others[name]["read_only_kernel_same_cold_bytes_us"] = floor * 1e6
         extra["other_configs_gemm_only_warm"] = others
     out["extra"] = extra
 
