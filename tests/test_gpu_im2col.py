@@ -105,3 +105,43 @@ def test_im2col_packed_headline_geometry():
                     assert np.array_equal(blk, Fref[b, iy, ix]), (b, oy, ox, ky, kx)
                 else:
                     assert not blk.any(), (b, oy, ox, ky, kx)
+
+
+@pytest.mark.parametrize("out_planes", [2, 1])
+def test_two_convolution_layers_stay_packed(out_planes):
+    """Layer 1 (3x3, pad 1) with the activation threshold fused into the product, layer 2 (3x3, stride 2) on its
+    packed output: the feature map between the layers exists only as packed words.  Oracle: direct convolution,
+    threshold by definition, direct convolution."""
+    from oracle import requant
+    nb, H, W, C0, F1, F2 = 2, 12, 10, 64, 128, 40
+    ternary_mid = out_planes == 2
+    say(f"two conv layers on packed data, middle feature map {'ternary' if ternary_mid else 'binary'}")
+    fmap = _fmap("tnn", (nb, H, W, C0), seed=21)
+    w1, _ = synth.make_custom("tnn", F1, 1, 9 * C0, seed=22)
+    w2, _ = synth.make_custom("tnn", F2, 1, 9 * F1, seed=23)
+    rng = np.random.default_rng(24)
+    lo = rng.integers(-12, -2, size=F1).astype(np.int32)
+    hi = rng.integers(2, 12, size=F1).astype(np.int32)
+    # ---- oracle
+    c1 = oi.conv2d_direct(fmap, w1.reshape(F1, 3, 3, C0), 1, 1, 1, 1)            # (nb, H, W, F1)
+    C1 = np.ascontiguousarray(c1.reshape(nb * H * W, F1).T).astype(np.int32)     # (F1, pixels) as the product yields it
+    Y = requant.requantize(C1, lo, hi if ternary_mid else None, ternary_mid)     # (pixels, F1) int8
+    mid = Y.reshape(nb, H, W, F1)
+    OH, OW = oi.out_size(H, W, 3, 3, 2, 2, 0, 0)
+    want = oi.conv2d_direct(mid, w2.reshape(F2, 3, 3, F1), 2, 2, 0, 0)           # (nb, OH, OW, F2)
+    # ---- library: pack -> gather -> product + threshold -> gather -> product
+    Fp = lb.pack_ternary(torch.from_numpy(fmap).cuda(), nb * H * W, C0, C0, 1)
+    B1 = lb.im2col_packed(Fp, 2, nb, H, W, C0, 3, 3, 1, 1, 1, 1)
+    A1 = lb.pack_a("tnn", torch.from_numpy(w1).cuda())
+    Mid = lb.gemm_requant("tnn", out_planes, F1, nb * H * W, 9 * C0, A1, B1, torch.from_numpy(lo).cuda(),
+                          torch.from_numpy(hi).cuda() if ternary_mid else None)
+    torch.cuda.synchronize()
+    ref_mid = (bitref.pack_ternary(Y) if ternary_mid else bitref.pack_binary(Y)).reshape(-1)
+    assert np.array_equal(words(Mid), ref_mid)
+    B2 = lb.im2col_packed(Mid, out_planes, nb, H, W, F1, 3, 3, 2, 2, 0, 0)
+    kind2 = "tnn" if ternary_mid else "tbn"                                      # ternary filters x binary map
+    A2 = lb.pack_a(kind2, torch.from_numpy(w2).cuda())
+    C2 = lb.gemm(kind2, F2, nb * OH * OW, 9 * F1, A2, B2)
+    torch.cuda.synchronize()
+    got = C2.cpu().numpy().reshape(F2, nb, OH, OW).transpose(1, 2, 3, 0)
+    assert np.array_equal(got, want)
