@@ -391,7 +391,7 @@ template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
 __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *__restrict__ Sp,
                                                                const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
                                                                int KW, int K, int32_t *__restrict__ C, int64_t ldc,
-                                                               int nSB, int nVB, int tiles_per_xcd,
+                                                               int nSB, int nVB, int tiles_per_xcd, int vb_fastest,
                                                                const int32_t *__restrict__ q_lo,
                                                                const int32_t *__restrict__ q_hi,
                                                                uint64_t *__restrict__ q_out, int q_planes)
@@ -401,12 +401,21 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
     __shared__ int32_t nnz_lds[L::NNZ];
 
     // XCD-aware tile order: consecutive workgroup ids go to different XCDs, so give each XCD a contiguous
-    // range of tiles; within it the S blocks of one V tile are adjacent and share that XCD's L2.
+    // range of tiles.  Within it the tiles that share a block of the LARGER operand are adjacent, so that operand is
+    // streamed from HBM once and the smaller one stays in that XCD's L2: the S blocks of one V tile when V is the
+    // larger operand, the V blocks of one S block (vb_fastest) when S is.
     const int bid = blockIdx.x;
     const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
     if ((bid >> 3) >= tiles_per_xcd || idx >= nSB * nVB)
         return;
-    const int vb = idx / nSB, sb = idx - vb * nSB;
+    int vb, sb;
+    if (vb_fastest) {
+        sb = idx / nVB;
+        vb = idx - sb * nVB;
+    } else {
+        vb = idx / nSB;
+        sb = idx - vb * nSB;
+    }
     gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, K, C, ldc, sb, vb, TR, q_lo, q_hi,
                                                             q_out, q_planes, lds, nnz_lds);
 }
@@ -447,9 +456,11 @@ hipError_t launch(const GemmArgs &a)
     const int64_t grid = (int64_t)tiles_per_xcd * 8;
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
+    // bytes per string: S strings have Traits::SD dwords per depth word, V strings Traits::VD
+    const int vb_fastest = (int64_t)a.rowsS * Traits<KIND>::SD > (int64_t)a.rowsV * Traits<KIND>::VD;
     hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, SG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
-                       a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd, a.q_lo,
-                       a.q_hi, a.q_out, a.q_planes);
+                       a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd, vb_fastest,
+                       a.q_lo, a.q_hi, a.q_out, a.q_planes);
     return hipGetLastError();
 }
 
