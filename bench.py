@@ -307,9 +307,6 @@ def main() -> int:
         extra["pack_a_us"] = tpa * 1e6
         extra["pack_b_us"] = tpb * 1e6
         extra["pack_b_gbs"] = (B.nbytes + Bp.numel() * 8) / tpb / 1e9
-        ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
-        extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
-        extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
         # product with the activation threshold fused into the epilogue (packed ternary output instead of int32 C)
         qlo = torch.full((M,), -20, dtype=torch.int32, device="cuda")
         qhi = torch.full((M,), 20, dtype=torch.int32, device="cuda")
@@ -318,19 +315,6 @@ def main() -> int:
         extra["gemm_requant_ternary_ms"] = trq * 1e3
         extra["gemm_requant_ternary_tops"] = w.ops / trq / 1e12
         del qout
-        # the same comparator with unsigned operands and zero points (eq. (3) corrections in the epilogue)
-        uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)      # {-1,0,1} -> {0,1,2}, zero point 1
-        tu8 = dev_time(lambda: lb.gemm_u8_mfma(M, N, K, uA, K, uB, N, 1, 1, C, N), 20)
-        extra["u8_zero_point_mfma_tops"] = w.ops / tu8 / 1e12
-        del uA, uB
-        # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
-        try:
-            torch._int_mm(dA, dB)
-            tlib = dev_time(lambda: torch._int_mm(dA, dB), 10)
-            extra["library_int8_gemm_tops"] = w.ops / tlib / 1e12
-        except Exception as e:  # not available on every build
-            extra["library_int8_gemm_tops"] = None
-            extra["library_int8_gemm_error"] = str(e)[:120]
         # convolution lowering on packed words: the same right operand built from a channel-packed 16x56x56x512
         # feature map (pack the map, gather words) instead of packing the unrolled 4608 x 50176 int8 matrix
         nb, FH, FW, FC = 16, 56, 56, 512
@@ -349,6 +333,24 @@ def main() -> int:
         extra["conv_lowering_on_packed_words"] = {"pack_feature_map_us": tfm * 1e6, "im2col_packed_us": tic * 1e6,
                                                   "step_ms": tcs * 1e3, "step_tops": w.ops / tcs / 1e12}
         del fmap, Fp
+        # matrix-core comparator last: the clock stays low for a while after MFMA-heavy kernels, which would
+        # otherwise colour the VALU-bound measurements above
+        ti8 = dev_time(lambda: lb.gemm_i8_mfma(M, N, K, dA, K, dB, N, C, N), 20)
+        extra["int8_mfma_tops"] = w.ops / ti8 / 1e12
+        extra["gemm_tnn_speedup_vs_int8_mfma"] = ti8 / gemm_s
+        # the same comparator with unsigned operands and zero points (eq. (3) corrections in the epilogue)
+        uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)      # {-1,0,1} -> {0,1,2}, zero point 1
+        tu8 = dev_time(lambda: lb.gemm_u8_mfma(M, N, K, uA, K, uB, N, 1, 1, C, N), 20)
+        extra["u8_zero_point_mfma_tops"] = w.ops / tu8 / 1e12
+        del uA, uB
+        # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
+        try:
+            torch._int_mm(dA, dB)
+            tlib = dev_time(lambda: torch._int_mm(dA, dB), 10)
+            extra["library_int8_gemm_tops"] = w.ops / tlib / 1e12
+        except Exception as e:  # not available on every build
+            extra["library_int8_gemm_tops"] = None
+            extra["library_int8_gemm_error"] = str(e)[:120]
         others = {}
         del dB, Bp, C
         for name, ww in synth.WORKLOADS.items():
