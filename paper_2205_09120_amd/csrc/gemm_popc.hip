@@ -474,9 +474,9 @@ hipError_t launch(const GemmArgs &a)
 const GemmVariant kBnn[] = {
     LB_VARIANT(1, KIND_BNN, 4, 1, 4, 16, 8),
     LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 4),
-    LB_VARIANT(3, KIND_BNN, 8, 2, 8, 8, 4),
+    LB_VARIANT(4, KIND_BNN, 8, 2, 8, 8, 4),
     LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8, 4),
-    LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 4),
+    LB_VARIANT(3, KIND_BNN, 8, 2, 4, 8, 4),
     LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8, 2),
     LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
 };
