@@ -85,7 +85,7 @@ def grid_scenario(args, torch, lb, synth) -> int:
     from HIP-graph replays (20 launches per graph).  Prints mean_over_shapes(T_row / T_col) like the paper's Table III.
     On a 256-CU GPU every one of these problems is launch-latency-bound, so the ratios are close to 1."""
     import numpy as np
-    algos = ["int8_mfma", "tnn", "tbn", "bnn"]
+    algos = ["int8_mfma", "library_int8", "tnn", "tbn", "bnn"]
     times = {a: [] for a in algos}
 
     def graph_time(fn, per_graph=20, replays=10):
@@ -121,6 +121,10 @@ def grid_scenario(args, torch, lb, synth) -> int:
             times[kind].append(graph_time(lambda: lb.gemm(kind, H, W, D, Ap, Bp, C, W)))
             if kind == "tnn":
                 times["int8_mfma"].append(graph_time(lambda: lb.gemm_i8_mfma(H, W, D, dA, D, dB, W, C, W)))
+                try:
+                    times["library_int8"].append(graph_time(lambda: torch._int_mm(dA, dB, out=C)))
+                except Exception:
+                    times["library_int8"].append(float("nan"))
     ratio = {b: {a: float(np.mean(np.array(times[b]) / np.array(times[a]))) for a in algos} for b in algos}
     # the same 64 products as ONE grouped launch per operand class
     grouped = {}
@@ -348,6 +352,7 @@ def main() -> int:
             torch._int_mm(dA, dB)
             tlib = dev_time(lambda: torch._int_mm(dA, dB), 10)
             extra["library_int8_gemm_tops"] = w.ops / tlib / 1e12
+            extra["gemm_tnn_speedup_vs_faster_int8_kernel"] = min(ti8, tlib) / gemm_s
         except Exception as e:  # not available on every build
             extra["library_int8_gemm_tops"] = None
             extra["library_int8_gemm_error"] = str(e)[:120]
@@ -362,6 +367,12 @@ def main() -> int:
             c_ = torch.empty((ww.M, ww.N), dtype=torch.int32, device="cuda")
             t = graph_time(lambda: lb.gemm(ww.kind, ww.M, ww.N, ww.K, ap_, bp_, c_, ww.N), 20, 20)
             t8 = graph_time(lambda: lb.gemm_i8_mfma(ww.M, ww.N, ww.K, da, ww.K, db, ww.N, c_, ww.N), 20, 20)
+            # the vendor library's int8 GEMM on the same operands, timed the same way (None where it refuses the shape
+            # or cannot be captured); the speed-up is quoted against the faster of the two 8-bit kernels
+            try:
+                tlib = graph_time(lambda: torch._int_mm(da, db, out=c_), 20, 20)
+            except Exception:
+                tlib = None
             packed_bytes = (ap_.numel() + bp_.numel()) * 8 + c_.numel() * 4
             cold = None
             if name.startswith("cfg5_"):
@@ -378,6 +389,8 @@ def main() -> int:
                 del copies
             others[name] = {"gemm_us": t * 1e6, "tops": ww.ops / t / 1e12, "int8_mfma_us": t8 * 1e6,
                             "speedup_vs_int8_mfma": t8 / t,
+                            "library_int8_us": None if tlib is None else tlib * 1e6,
+                            "speedup_vs_faster_int8_kernel": (t8 if tlib is None else min(t8, tlib)) / t,
                             "valu_frac": ww.M * ww.N * (ww.K / 32.0) * LANE_INSTR[ww.kind] / t / 1e12 / VALU_PEAK_TOPS,
                             "hbm_frac": packed_bytes / t / 1e9 / HBM_PEAK_GBS}
             if cold is not None:

@@ -946,14 +946,15 @@ void i8_force_tile(int t) { g_i8_forced = t; }
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    // the 256 x 128 tile needs enough tiles to fill the 256 compute units; smaller problems use 128 x 128
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    // the 256 x 128 instances (one workgroup per compute unit) pay off from about half a machine of tiles; smaller
+    // problems use the 4-wave 128 x 128 tile
+    const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
     int t = g_i8_forced;
     // a right operand of at most 16 columns would leave a matrix-core tile almost empty: stream A with dot products
     if (t < 0 && N <= 16 && M >= 64)
         return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
     if (t < 0)
-        t = big_tiles >= 512 ? 7 : 0;
+        t = tiles >= 128 ? 7 : 0;
     if (t >= 6) {
         const hipError_t e = t == 6 ? launch_dl<4, 64, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
                                     : launch_dl<3, 128, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
@@ -980,9 +981,9 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
 hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
                           int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
     const int8_t *a = reinterpret_cast<const int8_t *>(A), *b = reinterpret_cast<const int8_t *>(B);
-    if (big_tiles >= 512) {
+    if (tiles >= 128) {
         hipError_t e = launch_dl<3, 128, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
         if (e != hipErrorNotSupported)
             return e;
