@@ -580,7 +580,7 @@ int lb_num_variants(int op)
     if (op == 3)
         return lowbit::skinny_num_configs();
     if (op == 4)
-        return 8;
+        return 10;
     if (op < 0 || op > 2)
         return 0;
     lowbit::gemm_variants(op, &count);

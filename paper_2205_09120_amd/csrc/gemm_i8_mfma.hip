@@ -3,11 +3,12 @@
 // Comparison point for the popcount kernels: it computes the same C = A B from unpacked int8 operands, the role
 // the 8-bit gemmlowp multiplication (U8) plays in Section IV of the paper.
 //
-// Two kernels share the tile layouts described here.  gemm_i8_mfma_kernel: workgroup = 4 waves in a 2 x 2
-// arrangement; a wave computes TM x TN MFMA tiles of 32 x 32, so the workgroup tile is (64*TM) x (64*TN); depth step
-// 64 (two MFMA depth steps of 32); instances 128 x 128 (TM=TN=2, the default for small and ragged problems),
+// Three kernels.  The first two share the tile layouts described here.  gemm_i8_mfma_kernel: workgroup = 4 waves in
+// a 2 x 2 arrangement; a wave computes TM x TN MFMA tiles of 32 x 32, so the workgroup tile is (64*TM) x (64*TN);
+// depth step 64 (two MFMA depth steps of 32); instances 128 x 128 (TM=TN=2, what unaligned operands fall back to),
 // 256 x 128 and 256 x 256 (selectable).  gemm_i8_ws_kernel (further down): the 256 x 128 tile with the loading and
-// the multiplying done by different waves, the default for large problems.
+// the multiplying done by different waves.  gemm_i8_dl_kernel (last): operands go from global memory straight into
+// LDS; the default for aligned operands of any size.
 //   A (row-major, depth contiguous) is staged as is:  As[row][64 depth bytes (+16 pad)]; an operand fragment
 //   (16 depth bytes of one row per lane) is one ds_read_b128, conflict-free with the 80-byte row stride.
 //   B (row-major, depth strided) is transposed on the way: a thread loads 16 depth rows x 4 columns (16 dwords,
@@ -587,7 +588,9 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Direct-to-LDS instance for large, aligned, whole-tile problems: 256 x 128 tile, 8 waves.
+// Direct-to-LDS kernel, the default whenever every 16-byte chunk of the operands is aligned: 8 waves, tile
+// (64*TM) x (64*TN) with instances 256 x 128 (large problems), 128 x 128 and 64 x 64 (small ones, where more and
+// smaller workgroups hide the latency of a short depth loop better).
 //
 // In the kernels above every operand byte crosses the register file twice (global -> VGPR -> LDS -> VGPR), and the
 // returns of the global loads and of the LDS fragment reads share the way into the registers: measured on the
@@ -598,8 +601,8 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 //           ds_read_b128 of an MFMA A fragment (32 consecutive rows, one chunk) spreads over all banks.  With
 //           BKB = 128 a row of the tile is one whole 128-byte cache line of A; half lines (BKB = 64) move through
 //           the caches at about half the rate, which is why the 128-byte stage is the default.
-//   B tile  [depth row][128 column bytes] as in memory (no transpose on the way in), chunk c of depth row r stored
-//           at slot c ^ (r & 7).  The MFMA B fragment (16 depth bytes of one column per lane) is read with the
+//   B tile  [depth row][64*TN column bytes] as in memory (no transpose on the way in), chunk c of depth row r stored
+//           at slot c ^ (r & 7) (128 columns) or c ^ ((r >> 2) & 3) (64 columns).  The MFMA B fragment (16 depth bytes of one column per lane) is read with the
 //           transposing LDS read ds_read_b64_tr_b8: 16 lanes hand in the addresses of 8 rows x 16 bytes (lanes 2m and
 //           2m+1 the two halves of row m) and lane i receives byte i of each of the 8 rows.
 // The swizzles cost nothing: a lane of a direct load may fetch any global chunk, only its LDS slot is fixed.
@@ -608,24 +611,31 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 // step k"; a loader waits for its own loads of step k (vmcnt) before barrier k and refills the stage of step k - 1
 // after it, which every consumer has finished reading by then.  Unsigned operands (U8): the bytes cannot be re-biased
 // on the way in, so the consumers do it on the fragments and also take the byte sums of eq. (3) from them.
-template <int STAGES, int BKB, bool U8>
-__global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__restrict__ A, int64_t lda,
+// RAGGED: rows beyond M and column chunks beyond N are fetched from the last valid row / chunk instead (always in
+// bounds; the products they feed are never stored) and the stores are guarded; N must be a multiple of 16.
+template <int STAGES, int BKB, bool U8, int TM, int TN, bool RAGGED>
+__global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int M, int N, int K, const int8_t *__restrict__ A, int64_t lda,
                                                          const int8_t *__restrict__ B, int64_t ldb,
                                                          int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB,
                                                          int tiles_per_xcd, int zA, int zB)
 {
     constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;  // unsigned byte -> signed byte minus 128
-    constexpr int TM = 4, TN = 2;
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 64 * TM, BN = 64 * TN;             // 2 x 2 consumer waves of TM x TN MFMA tiles each
     constexpr int KS = BKB / 32;                          // MFMA depth steps per stage
     constexpr int CA = BKB / 16;                          // 16-byte chunks per A row
     constexpr int RA = 64 / CA;                           // A rows per wave-wide load
     constexpr int SH = CA == 4 ? 2 : 1;                   // A slot swizzle: chunk ^ ((row >> SH) & (CA - 1))
+    constexpr int CB = BN / 16;                           // 16-byte chunks per B row
+    constexpr int RB = 64 / CB;                           // B depth rows per wave-wide load
     constexpr int A_BYTES = BM * BKB, B_BYTES = BKB * BN;
     constexpr int STAGE = A_BYTES + B_BYTES;
     constexpr int A_LOADS = A_BYTES / 1024 / 4, B_LOADS = B_BYTES / 1024 / 4;  // per loader wave and step
     constexpr int LOADS = A_LOADS + B_LOADS;
-    static_assert(BN == 128 && (BKB == 64 || BKB == 128), "slot arithmetic below assumes 8 chunks per B row");
+    static_assert((BKB == 64 || BKB == 128) && (CB == 4 || CB == 8) && A_LOADS >= 1 && B_LOADS >= 1,
+                  "tile shapes the slot arithmetic below covers");
+    // B slot swizzle: chunk c of depth row r sits in slot c ^ fB(r); eight consecutive rows must land on different
+    // bank groups for the transposing read (row stride 128 bytes: r & 7; 64 bytes: (r >> 2) & 3)
+    auto fB = [](int r) { return CB == 8 ? (r & 7) : ((r >> 2) & 3); };
 
     __shared__ __attribute__((aligned(1024))) uint8_t smem[STAGES * STAGE];
     __shared__ uint32_t sums[U8 ? (BM + BN) * 2 : 1];  // U8: unsigned byte sums, [row or column][depth half of the lane]
@@ -645,27 +655,37 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
         const int w = wave - 4;
         // A: wave-wide load q covers rows RA*q .. RA*q+RA-1; this wave issues q = A_LOADS*w .. A_LOADS*w + A_LOADS-1.
         // With 8 chunks per row the swizzle term (row >> 1) & 7 has a bit that alternates with q.
+        // B: wave-wide load q covers depth rows RB*q .. RB*q+RB-1; this wave issues q = B_LOADS*w .. + B_LOADS-1.
+        // Ragged tiles: rows / column chunks beyond the matrix re-read the last valid ones (their products are
+        // never stored); the depth is always whole.
         const int a_row = lane / CA, a_slot = lane % CA;
-        const int a_chunk0 = a_slot ^ ((a_row >> SH) & (CA - 1));
-        const int a_chunk1 = CA == 8 ? (a_chunk0 ^ 4) : a_chunk0;            // odd q when RA = 8
-        const int8_t *a_base = A + (int64_t)(m0 + RA * A_LOADS * w + a_row) * lda;
-        // B: wave-wide load q covers depth rows 8q .. 8q+7; this wave issues q = B_LOADS*w .. B_LOADS*w + B_LOADS-1
-        const int b_row = lane >> 3;
-        const int b_chunk = (lane & 7) ^ b_row;
-        const int8_t *b_base = B + (int64_t)(8 * B_LOADS * w + b_row) * ldb + n0 + b_chunk * 16;
+        const int b_row = lane / CB, b_slot = lane % CB;
+        const int8_t *pa0[A_LOADS], *pb0[B_LOADS];
+#pragma unroll
+        for (int q = 0; q < A_LOADS; ++q) {
+            const int rl = RA * (A_LOADS * w + q) + a_row;               // row inside the tile
+            int row = m0 + rl;
+            if (RAGGED)
+                row = row < M ? row : M - 1;
+            pa0[q] = A + (int64_t)row * lda + ((a_slot ^ ((rl >> SH) & (CA - 1))) << 4);
+        }
+        int ncol = n0 + ((b_slot ^ fB(b_row)) << 4);                      // fB(RB*q + b_row) == fB(b_row)
+        if (RAGGED)
+            ncol = ncol + 16 <= N ? ncol : N - 16;
+#pragma unroll
+        for (int q = 0; q < B_LOADS; ++q)
+            pb0[q] = B + (int64_t)(RB * (B_LOADS * w + q) + b_row) * ldb + ncol;
         auto issue = [&](int step) __attribute__((always_inline)) {
             uint8_t *st = smem + (step % STAGES) * STAGE;
-            const int8_t *pa = a_base + (int64_t)step * BKB;
-            const int8_t *pb = b_base + (int64_t)step * BKB * ldb;
 #pragma unroll
             for (int q = 0; q < A_LOADS; ++q)
                 __builtin_amdgcn_global_load_lds(
-                    (const void __attribute__((address_space(1))) *)(pa + (int64_t)(RA * q) * lda + ((q & 1) ? a_chunk1 : a_chunk0) * 16),
+                    (const void __attribute__((address_space(1))) *)(pa0[q] + (int64_t)step * BKB),
                     (void __attribute__((address_space(3))) *)(st + (A_LOADS * w + q) * 1024), 16, 0, 0);
 #pragma unroll
             for (int q = 0; q < B_LOADS; ++q)
                 __builtin_amdgcn_global_load_lds(
-                    (const void __attribute__((address_space(1))) *)(pb + (int64_t)(8 * q) * ldb),
+                    (const void __attribute__((address_space(1))) *)(pb0[q] + (int64_t)step * BKB * ldb),
                     (void __attribute__((address_space(3))) *)(st + A_BYTES + (B_LOADS * w + q) * 1024), 16, 0, 0);
         };
         constexpr int AHEAD = STAGES - 1;
@@ -719,8 +739,8 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
         const int jj = lane & 15;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const int row = 16 * khalf + 8 * r + (jj >> 1);  // + 32*ks: leaves row & 7 unchanged
-            b_off[j][r] = A_BYTES + row * BN + ((chunk ^ (row & 7)) << 4) + 8 * (jj & 1);
+            const int row = 16 * khalf + 8 * r + (jj >> 1);  // + 32*ks, which leaves fB(row) unchanged
+            b_off[j][r] = A_BYTES + row * BN + ((chunk ^ fB(row)) << 4) + 8 * (jj & 1);
         }
     }
     auto read_frags = [&](int stage, int ks, v4i(&af)[TM], v4i(&bf)[TN]) __attribute__((always_inline)) {
@@ -743,7 +763,13 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
     // block.  The main loop is instantiated once per role (no per-instruction selects), and the preparation of row
     // i+1 issues behind the MFMAs of row i.
     const bool sum_a = U8 && wm == wn, sum_b = U8 && wm != wn;
-    uint32_t rs[TM] = {0u, 0u, 0u, 0u}, cs[TN] = {0u, 0u};
+    uint32_t rs[TM], cs[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        rs[i] = 0u;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+        cs[j] = 0u;
     auto flip = [&](v4i &f) __attribute__((always_inline)) {
         f = v4i{(int)((uint32_t)f[0] ^ FLIP), (int)((uint32_t)f[1] ^ FLIP), (int)((uint32_t)f[2] ^ FLIP), (int)((uint32_t)f[3] ^ FLIP)};
     };
@@ -853,7 +879,8 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int K, const int8_t *__
                 int32_t out = acc[i][j][r];
                 if constexpr (U8)
                     out += ccorr - zB * ((int32_t)(rsum[lrow * 2] + rsum[lrow * 2 + 1]) - 128 * K);
-                C[(int64_t)(m0 + lrow) * ldc + col] = out;
+                if (!RAGGED || (m0 + lrow < M && col < N))
+                    C[(int64_t)(m0 + lrow) * ldc + col] = out;
             }
         }
 }
@@ -915,26 +942,53 @@ hipError_t launch_ws(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t l
     return hipGetLastError();
 }
 
-// Direct-to-LDS 256 x 128 instance; hipErrorNotSupported unless the tiles are whole and every 16-byte chunk aligned.
-template <int STAGES, int BKB, bool U8>
+// Direct-to-LDS instances; hipErrorNotSupported unless every 16-byte chunk is aligned, the depth is a whole number
+// of stages and (RAGGED = false) the tiles are whole.
+template <int STAGES, int BKB, bool U8, int TM, int TN, bool RAGGED>
 hipError_t launch_dl(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                      int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
 {
-    constexpr int BM = 256, BN = 128;
-    const bool ok = (M % BM) == 0 && (N % BN) == 0 && (K % BKB) == 0 && K >= BKB &&
-                    (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
-                    (reinterpret_cast<uintptr_t>(B) % 16 == 0) && (ldb % 16 == 0);
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const bool ok = (K % BKB) == 0 && K >= BKB && (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
+                    (reinterpret_cast<uintptr_t>(B) % 16 == 0) && (ldb % 16 == 0) &&
+                    (RAGGED ? ((N % 16) == 0 && N >= 16) : ((M % BM) == 0 && (N % BN) == 0));
     if (!ok)
         return hipErrorNotSupported;
-    const int nMB = (int)(M / BM), nNB = (int)(N / BN);
+    const int nMB = (int)((M + BM - 1) / BM), nNB = (int)((N + BN - 1) / BN);
     const int64_t tiles = (int64_t)nMB * nNB;
     const int tiles_per_xcd = (int)((tiles + 7) / 8);
     const int64_t grid = (int64_t)tiles_per_xcd * 8;
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_i8_dl_kernel<STAGES, BKB, U8>), dim3((unsigned)grid), dim3(512), 0, stream, (int)K, A, lda, B,
-                       ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
+    hipLaunchKernelGGL((gemm_i8_dl_kernel<STAGES, BKB, U8, TM, TN, RAGGED>), dim3((unsigned)grid), dim3(512), 0, stream,
+                       (int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     return hipGetLastError();
+}
+
+// Shape-based choice among the direct-to-LDS instances (thresholds from sweeps over conv-shaped problems): 256 x 128
+// tiles from half a machine of them up, otherwise 128 x 128 from about 112 tiles up, otherwise 64 x 64 (small
+// problems are latency-bound: more, smaller workgroups win); depth stages of 128 bytes when the depth allows, else 64.
+template <bool U8>
+hipError_t launch_dl_auto(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                          int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
+{
+    const int64_t t256 = ((M + 255) / 256) * ((N + 127) / 128);
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const bool whole256 = (M % 256) == 0 && (N % 128) == 0;
+    if (K % 128 == 0) {
+        if (t256 >= 128)
+            return whole256 ? launch_dl<3, 128, U8, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB)
+                            : launch_dl<3, 128, U8, 4, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+        if (t128 >= 112)
+            return launch_dl<3, 128, U8, 2, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+        return launch_dl<3, 128, U8, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+    }
+    if (K % 64 == 0) {
+        if (t256 >= 128 && whole256)
+            return launch_dl<4, 64, U8, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+        return launch_dl<4, 64, U8, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+    }
+    return hipErrorNotSupported;
 }
 
 int g_i8_forced = -1;
@@ -946,18 +1000,23 @@ void i8_force_tile(int t) { g_i8_forced = t; }
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    // the 256 x 128 instances (one workgroup per compute unit) pay off from about half a machine of tiles; smaller
-    // problems use the 4-wave 128 x 128 tile
     const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
     int t = g_i8_forced;
     // a right operand of at most 16 columns would leave a matrix-core tile almost empty: stream A with dot products
     if (t < 0 && N <= 16 && M >= 64)
         return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
-    if (t < 0)
-        t = tiles >= 128 ? 7 : 0;
+    if (t < 0) {
+        // direct-to-LDS instances wherever alignment and depth allow, then the register-staged ones
+        const hipError_t e = launch_dl_auto<false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+        if (e != hipErrorNotSupported)
+            return e;
+        t = tiles >= 128 ? 3 : 0;
+    }
     if (t >= 6) {
-        const hipError_t e = t == 6 ? launch_dl<4, 64, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
-                                    : launch_dl<3, 128, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+        const hipError_t e = t == 6   ? launch_dl<4, 64, false, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                             : t == 7 ? launch_dl<3, 128, false, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                             : t == 8 ? launch_dl<3, 128, false, 2, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                                      : launch_dl<3, 128, false, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
         if (e != hipErrorNotSupported)
             return e;
         t = 3;
@@ -983,10 +1042,10 @@ hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int
 {
     const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
     const int8_t *a = reinterpret_cast<const int8_t *>(A), *b = reinterpret_cast<const int8_t *>(B);
+    hipError_t e = launch_dl_auto<true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
+    if (e != hipErrorNotSupported)
+        return e;
     if (tiles >= 128) {
-        hipError_t e = launch_dl<3, 128, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
-        if (e != hipErrorNotSupported)
-            return e;
         e = launch_ws<true, 3>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
         if (e != hipErrorNotSupported)
             return e;

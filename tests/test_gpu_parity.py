@@ -228,7 +228,8 @@ def test_deterministic():
                                    (4096, 8, 2048), (100, 5, 3000), (64, 16, 4100), (257, 9, 16), (1000, 8, 8192),
                                    (256, 128, 64), (512, 256, 128), (256, 384, 192), (512, 128, 448), (300, 516, 144),
                                    (20, 24, 16), (700, 260, 1040), (256, 256, 128), (512, 512, 384),
-                                   (256, 768, 1280), (768, 256, 256)])
+                                   (256, 768, 1280), (768, 256, 256), (257, 304, 256), (100, 48, 192),
+                                   (130, 1040, 384), (513, 3088, 256), (65, 16, 64), (1, 32, 128)])
 def test_i8_mfma(M, N, K):
     say(f"gemm_i8_mfma M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
@@ -245,7 +246,8 @@ def test_i8_mfma(M, N, K):
         lb.lb_set_variant(4, -1)
 
 
-@pytest.mark.parametrize("M,N,K", [(2048, 16384, 192), (2048, 16512, 208), (2300, 16384, 64), (2048, 16384, 384)])
+@pytest.mark.parametrize("M,N,K", [(2048, 16384, 192), (2048, 16512, 208), (2300, 16384, 64), (2048, 16384, 384),
+                                   (1100, 4112, 256), (640, 6416, 128), (2048, 2064, 384)])
 def test_i8_and_u8_large_default_path(M, N, K):
     """Shapes large enough for the shape-based choice to take the direct-to-LDS kernel (whole tiles, depth a multiple
     of 128) or the wave-specialised one (everything else, ragged tiles included)."""
@@ -332,7 +334,8 @@ def test_sparse_and_dense_ternary_extremes():
 # ------------------------------------------------------------------------------------------------ U8 with zero points (eq. (3))
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (257, 300, 1000), (512, 784, 2304),
-                                   (33, 8, 4096), (300, 515, 131), (1024, 2048, 320)])
+                                   (33, 8, 4096), (300, 515, 131), (1024, 2048, 320), (257, 304, 256), (100, 48, 192),
+                                   (513, 3088, 384), (1100, 4112, 128)])
 def test_u8_zero_point_gemm(M, N, K):
     rng = np.random.default_rng(M * 3 + N * 5 + K)
     A = rng.integers(0, 256, size=(M, K), dtype=np.uint8)
