@@ -28,6 +28,7 @@ constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K m
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
 constexpr int64_t kSkinnyMax = 16;             // widest "skinny" side served by the depth-split kernel
+constexpr int kI8Instances = 10;               // kernel instances of gemm_i8_mfma selectable through lb_set_variant
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -555,7 +556,7 @@ int lb_set_variant(int op, int variant)
 {
     int count = 0;
     if (op == 4) {
-        if (variant < -1 || variant > 11)
+        if (variant < -1 || variant >= kI8Instances)
             return fail(LB_EINVAL, "lb_set_variant: int8 tile %d out of range", variant);
         lowbit::i8_force_tile(variant);
         return LB_OK;
@@ -580,7 +581,7 @@ int lb_num_variants(int op)
     if (op == 3)
         return lowbit::skinny_num_configs();
     if (op == 4)
-        return 10;
+        return kI8Instances;
     if (op < 0 || op > 2)
         return 0;
     lowbit::gemm_variants(op, &count);
