@@ -130,6 +130,20 @@ LB_API int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const u
              void *stream);
 
 /*
+ * gemm_c16 -- gemm_bnn / gemm_tnn / gemm_tbn writing a signed 16-bit C, the accumulator and output width of the
+ * paper's microkernels (Section III; Table II, k_max = 32767 for all three).  Since |c| <= K, the values are the ones
+ * the int32 calls write whenever K <= 32767; the C store, which dominates the traffic of shallow products, is halved.
+ *
+ *   kind   0 = BNN, 1 = TNN, 2 = TBN operands (Ap, Bp as for the corresponding gemm_* call)
+ *   C      device, int16, row-major M x N with leading dimension ldc >= N (in 16-bit elements), 2-byte aligned;
+ *          overwritten.
+ *   K      1 <= K <= 32767; a larger depth is LB_EOVERFLOW (eq. (4) with a signed 16-bit result).
+ * Everything else as for gemm_bnn / gemm_tnn / gemm_tbn.
+ */
+LB_API int gemm_c16(int kind, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int16_t *C,
+                    int64_t ldc, void *stream);
+
+/*
  * gemm_requant -- gemm_bnn / gemm_tnn / gemm_tbn with the activation threshold fused into the epilogue: instead of
  * the int32 matrix C the call writes the low-bit feature map the next layer consumes, already packed.  The paper's
  * algorithms stop at the integer C (Section III); this is the step that follows it in a BNN / TNN / TBN layer.

@@ -20,7 +20,7 @@ OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
 _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
-           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_grouped_table_bytes",
+           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
            "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         for f in (L.gemm_bnn, L.gemm_tnn, L.gemm_tbn):
             f.restype = ci
             f.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
+        L.gemm_c16.restype = ci
+        L.gemm_c16.argtypes = [ci, i64, i64, i64, vp, vp, vp, i64, vp]
         L.gemm_grouped_table_bytes.restype = ctypes.c_size_t
         L.gemm_grouped_table_bytes.argtypes = [ci, i64, vp]
         L.gemm_grouped_plan.restype = ci
@@ -178,6 +180,17 @@ def gemm_tnn(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
 
 def gemm_tbn(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
     return _gemm(lib().gemm_tbn, M, N, K, Ap, Bp, C, ldc, stream)
+
+
+def gemm_c16(kind, M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    """gemm_<kind> with a signed 16-bit C (K <= 32767)."""
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int16, device=Ap.device)
+        ldc = N
+    elif ldc is None:
+        ldc = C.stride(0) if C.dim() == 2 else N
+    _check(lib().gemm_c16(_OPS.get(kind, kind), M, N, K, _ptr(Ap), _ptr(Bp), _ptr(C), ldc, _stream(stream)))
+    return C
 
 
 def gemm_i8_mfma(M, N, K, A, lda, B, ldb, C=None, ldc=None, stream=None):

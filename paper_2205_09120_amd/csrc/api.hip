@@ -101,7 +101,7 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
 // Argument rules common to gemm_bnn / gemm_tnn / gemm_tbn and to every problem of a grouped launch.
 // *empty is set when there is nothing to compute (M == 0 or N == 0).
 int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
-               const int32_t *C, int64_t ldc, bool *empty)
+               const void *C, int64_t ldc, bool *empty, int c_bytes = 4)
 {
     *empty = false;
     if (M < 0 || N < 0)
@@ -120,10 +120,10 @@ int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t
         return fail(LB_EINVAL, "%s: null pointer", name);
     if (ldc < N)
         return fail(LB_EINVAL, "%s: ldc=%lld < N=%lld", name, (long long)ldc, (long long)N);
-    if (ldc > INT64_MAX / M / 4)
+    if (ldc > INT64_MAX / M / c_bytes)
         return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
-    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, 4))
-        return fail(LB_EINVAL, "%s: operands must be 16-byte aligned, C 4-byte aligned", name);
+    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, (uintptr_t)c_bytes))
+        return fail(LB_EINVAL, "%s: operands must be 16-byte aligned, C %d-byte aligned", name, c_bytes);
     return LB_OK;
 }
 
@@ -132,11 +132,12 @@ int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t
 // M is not.
 bool b_on_scalar_side(int kind, int64_t M, int64_t N) { return kind == lowbit::KIND_TBN || (N < 64 && M > N); }
 
+// c16: C is an int16_t matrix (passed as void through the int32_t pointer of the launch arguments).
 int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
-            int32_t *C, int64_t ldc, void *stream)
+            void *C, int64_t ldc, void *stream, bool c16 = false)
 {
     bool empty;
-    const int rc = check_gemm(name, M, N, K, Ap, Bp, C, ldc, &empty);
+    const int rc = check_gemm(name, M, N, K, Ap, Bp, C, ldc, &empty, c16 ? 2 : 4);
     if (rc != LB_OK || empty)
         return rc;
     const int64_t KW = (K + 63) / 64;
@@ -158,8 +159,9 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
             sa.rowsY = (int)(skinny_n ? N : M);
             sa.KW = (int)KW;
             sa.K = (int)K;
-            sa.C = C;
+            sa.C = static_cast<int32_t *>(C);
             sa.ldc = ldc;
+            sa.c16 = c16 ? 1 : 0;
             sa.stream = static_cast<hipStream_t>(stream);
             const hipError_t e = lowbit::launch_gemm_skinny(kind, sa, skinny_m);
             if (e != hipSuccess)
@@ -182,8 +184,9 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     }
     a.KW = (int)KW;
     a.K = (int)K;
-    a.C = C;
+    a.C = static_cast<int32_t *>(C);
     a.ldc = ldc;
+    a.c16 = c16 ? 1 : 0;
     a.stream = static_cast<hipStream_t>(stream);
     const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV);
     const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
@@ -272,6 +275,18 @@ int gemm_tbn(int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t
              void *stream)
 {
     return do_gemm(lowbit::KIND_TBN, "gemm_tbn", M, N, K, Ap, Bp, C, ldc, stream);
+}
+
+int gemm_c16(int kind, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp, int16_t *C, int64_t ldc,
+             void *stream)
+{
+    const char *name = "gemm_c16";
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    // |c| <= K for every kind, so a signed 16-bit C is exact up to the k_max of Table II
+    if (K > 32767)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 32767 (signed 16-bit C)", name, (long long)K);
+    return do_gemm(kind, name, M, N, K, Ap, Bp, C, ldc, stream, true);
 }
 
 size_t gemm_grouped_table_bytes(int kind, int64_t count, const lb_gemm_problem *problems)

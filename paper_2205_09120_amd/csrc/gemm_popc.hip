@@ -99,7 +99,7 @@ template <int KIND, int TV, int KG> struct TileLds {
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG, int TRM>
 __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, const uint32_t *__restrict__ Vp,
                                                int rowsS, int rowsV, int KW, int K, int32_t *__restrict__ C,
-                                               int64_t ldc, int sb, int vb, bool tr_rt,
+                                               int64_t ldc, int sb, int vb, bool tr_rt, bool c16,
                                                const int32_t *__restrict__ q_lo, const int32_t *__restrict__ q_hi,
                                                uint64_t *__restrict__ q_out, int q_planes,
                                                typename TileLds<KIND, TV, KG>::VVec *lds_base, int32_t *nnz_lds)
@@ -363,6 +363,35 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             }
         }
         if (v < rowsV) {
+            if (c16) {
+                // 16-bit C (the accumulator width of Section III; the host has checked K <= 32767, so |c| fits)
+                int16_t *C16 = reinterpret_cast<int16_t *>(C);
+                if (!tr) {
+#pragma unroll
+                    for (int i = 0; i < TS; ++i)
+                        if (s0 + i < rowsS)
+                            C16[(int64_t)(s0 + i) * ldc + v] = (int16_t)out[i];
+                } else {
+                    int16_t *crow = C16 + (int64_t)v * ldc + s0;
+                    bool done = false;
+                    if constexpr (TS % 4 == 0) {
+                        if (s0 + TS <= rowsS && ((reinterpret_cast<uintptr_t>(crow) & 7) == 0)) {
+#pragma unroll
+                            for (int i = 0; i < TS; i += 4)
+                                *reinterpret_cast<int2 *>(crow + i) =
+                                    make_int2((out[i] & 0xffff) | (out[i + 1] << 16), (out[i + 2] & 0xffff) | (out[i + 3] << 16));
+                            done = true;
+                        }
+                    }
+                    if (!done) {
+#pragma unroll
+                        for (int i = 0; i < TS; ++i)
+                            if (s0 + i < rowsS)
+                                crow[i] = (int16_t)out[i];
+                    }
+                }
+                continue;
+            }
             if (!tr) {
 #pragma unroll
                 for (int i = 0; i < TS; ++i)
@@ -392,7 +421,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                                                                const uint32_t *__restrict__ Vp, int rowsS, int rowsV,
                                                                int KW, int K, int32_t *__restrict__ C, int64_t ldc,
                                                                int nSB, int nVB, int tiles_per_xcd, int vb_fastest,
-                                                               const int32_t *__restrict__ q_lo,
+                                                               int c16, const int32_t *__restrict__ q_lo,
                                                                const int32_t *__restrict__ q_hi,
                                                                uint64_t *__restrict__ q_out, int q_planes)
 {
@@ -416,8 +445,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         vb = idx / nSB;
         sb = idx - vb * nSB;
     }
-    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, K, C, ldc, sb, vb, TR, q_lo, q_hi,
-                                                            q_out, q_planes, lds, nnz_lds);
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, K, C, ldc, sb, vb, TR, c16 != 0,
+                                                            q_lo, q_hi, q_out, q_planes, lds, nnz_lds);
 }
 
 // Grouped launch: many independent small problems in one grid.  The table (built on the host by plan_group) maps
@@ -443,7 +472,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_group_kernel(const GroupHeade
     const int local = (int)(bid - r.tile0);
     const int vb = local / r.nSB, sb = local - vb * r.nSB;
     gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 2>(r.Sp, r.Vp, r.rowsS, r.rowsV, r.KW, r.K, r.C, r.ldc, sb, vb,
-                                                   r.transposed != 0, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
+                                                   r.transposed != 0, false, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
 }
 
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
@@ -460,7 +489,7 @@ hipError_t launch(const GemmArgs &a)
     const int vb_fastest = (int64_t)a.rowsS * Traits<KIND>::SD > (int64_t)a.rowsV * Traits<KIND>::VD;
     hipLaunchKernelGGL((gemm_popc_kernel<KIND, TS, TV, WAVES, KG, SG, TR>), dim3((unsigned)grid), dim3(64 * WAVES), 0,
                        a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd, vb_fastest,
-                       a.q_lo, a.q_hi, a.q_out, a.q_planes);
+                       a.c16, a.q_lo, a.q_hi, a.q_out, a.q_planes);
     return hipGetLastError();
 }
 

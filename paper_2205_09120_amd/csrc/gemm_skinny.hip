@@ -85,7 +85,7 @@ template <int CNT, int BIT> __device__ __forceinline__ void reduce_halving(int32
 template <int KIND, int R, int WAVES, bool TR>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__restrict__ Xp_, const void *__restrict__ Yp_,
                                                           int rowsX, int rowsY, int KW, int K,
-                                                          int32_t *__restrict__ C, int64_t ldc)
+                                                          int32_t *__restrict__ C, int64_t ldc, int c16)
 {
     using T = SkTraits<KIND>;
     using XE = typename T::X;
@@ -220,10 +220,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
             int32_t out = val[0];
             if constexpr (KIND == KIND_BNN)
                 out = K - 2 * out;
-            if constexpr (!TR)
-                C[(int64_t)xr * ldc + yn] = out;
+            const int64_t at = TR ? (int64_t)yn * ldc + xr : (int64_t)xr * ldc + yn;
+            if (c16)
+                reinterpret_cast<int16_t *>(C)[at] = (int16_t)out;  // K <= 32767 checked on the host
             else
-                C[(int64_t)yn * ldc + xr] = out;
+                C[at] = out;
         }
     }
 }
@@ -235,7 +236,7 @@ template <int KIND, int R, int WAVES, bool TR> hipError_t launch_sk(const Skinny
     if (gx > 0x7fffffffLL || gy > 65535)
         return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((gemm_skinny_kernel<KIND, R, WAVES, TR>), dim3((unsigned)gx, (unsigned)gy), dim3(64 * WAVES),
-                       0, a.stream, a.Xp, a.Yp, a.rowsX, a.rowsY, a.KW, a.K, a.C, a.ldc);
+                       0, a.stream, a.Xp, a.Yp, a.rowsX, a.rowsY, a.KW, a.K, a.C, a.ldc, a.c16);
     return hipGetLastError();
 }
 

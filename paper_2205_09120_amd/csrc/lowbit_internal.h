@@ -18,6 +18,7 @@ struct GemmArgs {
     int32_t *C;
     int64_t ldc;
     hipStream_t stream;
+    int c16 = 0;  // 1: C is an int16_t matrix (ldc in 16-bit elements); the caller guarantees K <= 32767
     // Re-quantized output (transposed launcher only; q_out == nullptr selects the int32 store): instead of C, one
     // packed bit string per S row is written whose depth runs over the V rows, q_planes = 1 binary / 2 ternary,
     // thresholds per V row.
@@ -73,6 +74,7 @@ struct SkinnyArgs {
     int32_t *C;
     int64_t ldc;
     hipStream_t stream;
+    int c16 = 0;  // as in GemmArgs
 };
 hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed);
 int skinny_num_configs();

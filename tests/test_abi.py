@@ -60,6 +60,18 @@ def test_gemm_argument_validation(L):
     assert b"ldc" in L.lb_last_error() or b"aligned" in L.lb_last_error()
 
 
+def test_c16_argument_validation(L):
+    fake = 0x1000
+    f = L.gemm_c16
+    assert f(3, 4, 4, 64, fake, fake, fake, 4, None) == binding.LB_EINVAL           # no such operand class
+    assert f(1, 4, 4, 32768, fake, fake, fake, 4, None) == binding.LB_EOVERFLOW     # Table II: k_max = 32767
+    assert b"32767" in L.lb_last_error()
+    assert f(1, 4, 4, 0, fake, fake, fake, 4, None) == binding.LB_EINVAL
+    assert f(0, 4, 8, 64, fake, fake, fake, 7, None) == binding.LB_EINVAL           # ldc < N
+    assert f(2, 4, 4, 64, fake, fake, fake + 1, 4, None) == binding.LB_EINVAL       # C not 2-byte aligned
+    assert f(2, 0, 4, 64, None, None, None, 4, None) == binding.LB_OK               # empty problem
+
+
 def test_pack_argument_validation(L):
     fake = 0x1000
     for f in (L.pack_binary, L.pack_ternary):
@@ -146,6 +158,7 @@ def test_variant_hooks(L):
     assert L.lb_set_variant(3, -1) == binding.LB_OK
     assert L.lb_set_variant(3, L.lb_num_variants(3)) == binding.LB_EINVAL
     assert L.lb_set_variant(4, 0) == binding.LB_OK and L.lb_set_variant(4, -1) == binding.LB_OK
+    assert L.lb_set_variant(4, L.lb_num_variants(4)) == binding.LB_EINVAL
     assert L.lb_set_variant(5, 0) == binding.LB_EINVAL
     assert L.lb_num_variants(7) == 0
 

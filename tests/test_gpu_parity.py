@@ -221,6 +221,51 @@ def test_deterministic():
     assert np.array_equal(a, b)
 
 
+# ------------------------------------------------------------------------------------------------ 16-bit C (Section III)
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_c16_matches_oracle(kind):
+    """Signed 16-bit C: same integers as the oracle (|c| <= K <= 32767), on the tiled kernel in both orientations,
+    every tile variant, the skinny kernel, a padded ldc (padding untouched) and an odd C address."""
+    shapes = [(64, 256, 576), (130, 70, 100), (257, 300, 1000), (70, 40, 32767), (300, 8, 700), (9, 400, 260),
+              (512, 70, 64), (1, 1, 1), (33, 129, 65)]
+    for (M, N, K) in shapes:
+        A, B = synth.make_custom(kind, M, N, K, seed=M * 11 + N * 7 + K)
+        want = oracle.gemm(A, B)
+        assert np.abs(want).max() <= 32767
+        Ap, Bp = lb.pack_a(kind, dev(A)), lb.pack_b(kind, dev(B))
+        try:
+            for v in [-1] + list(range(lb.lb_num_variants(kind))):
+                lb.lb_set_variant(kind, v)
+                ldc = N + 3
+                say(f"gemm_c16 {kind} M={M} N={N} K={K} variant={v} ldc={ldc}")
+                flat = torch.full((M * ldc + 1,), 12345, dtype=torch.int16, device="cuda")
+                C = flat[1:].view(M, ldc)                             # 2-byte aligned only
+                lb.gemm_c16(kind, M, N, K, Ap, Bp, C, ldc)
+                torch.cuda.synchronize()
+                got = C.cpu().numpy()
+                assert got.dtype == np.int16
+                assert np.array_equal(got[:, :N].astype(np.int32), want), (M, N, K, v)
+                assert np.all(got[:, N:] == 12345) and int(flat[0]) == 12345
+        finally:
+            lb.lb_set_variant(kind, -1)
+
+
+def test_gemm_c16_extreme_values_and_depth_limit():
+    """K = 32767 with operands that reach +K and -K; K = 32768 is refused."""
+    K = 32767
+    A = np.ones((5, K), dtype=np.int8)
+    B = np.ones((K, 70), dtype=np.int8)
+    B[:, 1::2] = -1
+    say("gemm_c16 extremes")
+    for kind in ("bnn", "tnn", "tbn"):
+        got = lb.gemm_c16(kind, 5, 70, K, lb.pack_a(kind, dev(A)), lb.pack_b(kind, dev(B))).cpu().numpy()
+        assert np.all(got[:, 0::2] == K) and np.all(got[:, 1::2] == -K)
+    with pytest.raises(lb.LowbitError) as e:
+        lb.gemm_c16("bnn", 5, 70, K + 1, lb.pack_a("bnn", dev(A)), lb.pack_b("bnn", dev(B)))
+    assert e.value.status == lb.LB_EOVERFLOW
+
+
 # ------------------------------------------------------------------------------------------------ int8 matrix-core comparator
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (64, 256, 576), (130, 70, 100), (128, 128, 64), (257, 300, 1000),
@@ -262,6 +307,46 @@ def test_i8_and_u8_large_default_path(M, N, K):
     got = lb.gemm_u8_mfma(M, N, K, dev(Au), K, dev(Bu), N, 3, 250)
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy(), oracle.gemm_u8_zero_point(Au, Bu, 3, 250))
+
+
+def test_i8_u8_random_shapes_and_leading_dimensions():
+    """40 seeded draws through the shape-based dispatch of the 8-bit comparator: extents log-uniform, N and K often
+    multiples of 16 / 64 (the direct-to-LDS instances) and often not (the others), padded leading dimensions, C
+    padding must stay untouched."""
+    rng = np.random.default_rng(77)
+    for it in range(40):
+        M = int(np.exp(rng.uniform(0, np.log(900))))
+        N = int(np.exp(rng.uniform(0, np.log(1500))))
+        K = int(np.exp(rng.uniform(0, np.log(3000))))
+        if rng.random() < 0.6:
+            N = max(16, N // 16 * 16)
+        if rng.random() < 0.7:
+            K = max(64, K // 64 * 64)
+        lda = K + int(rng.choice([0, 16, 48, 5]))
+        ldb = N + int(rng.choice([0, 16, 64, 3]))
+        ldc = N + int(rng.choice([0, 4, 7]))
+        zA, zB = int(rng.integers(0, 256)), int(rng.integers(0, 256))
+        say(f"8-bit random {it}: M={M} N={N} K={K} lda={lda} ldb={ldb} ldc={ldc} zA={zA} zB={zB}")
+        A = np.zeros((M, lda), dtype=np.int8)
+        B = np.zeros((K, ldb), dtype=np.int8)
+        A[:, :K] = rng.integers(-128, 128, size=(M, K), dtype=np.int8)
+        B[:, :N] = rng.integers(-128, 128, size=(K, N), dtype=np.int8)
+        A[:, K:] = 77                                                     # padding must never reach a product
+        B[:, N:] = -55
+        C = torch.full((M, ldc), 4242, dtype=torch.int32, device="cuda")
+        lb.gemm_i8_mfma(M, N, K, dev(A), lda, dev(B), ldb, C, ldc)
+        torch.cuda.synchronize()
+        got = C.cpu().numpy()
+        assert np.array_equal(got[:, :N], oracle.gemm(np.ascontiguousarray(A[:, :K]), np.ascontiguousarray(B[:, :N])))
+        assert np.all(got[:, N:] == 4242)
+        Au, Bu = A.view(np.uint8), B.view(np.uint8)
+        C.fill_(4242)
+        lb.gemm_u8_mfma(M, N, K, dev(Au), lda, dev(Bu), ldb, zA, zB, C, ldc)
+        torch.cuda.synchronize()
+        got = C.cpu().numpy()
+        want = oracle.gemm_u8_zero_point(np.ascontiguousarray(Au[:, :K]), np.ascontiguousarray(Bu[:, :N]), zA, zB)
+        assert np.array_equal(got[:, :N], want)
+        assert np.all(got[:, N:] == 4242)
 
 
 def test_i8_mfma_on_ternary_config():
