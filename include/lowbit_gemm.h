@@ -241,9 +241,9 @@ LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, 
  *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
  *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel,
  *            4 = kernel instance of gemm_i8_mfma (0..2: 4-wave tiles 128x128, 256x256, 256x128; 3..5: wave-specialised
- *            256x128 with 3, 2, 4 depth steps of prefetch; 6, 7: direct-to-LDS 256x128 with 64- / 128-byte depth
- *            stages; 8, 9: direct-to-LDS 128x128 / 64x64 tiles, ragged extents allowed; an instance that cannot
- *            serve a shape falls back to the next simpler one)
+ *            256x128 with 3, 2, 4 depth steps of prefetch; 6: direct-to-LDS 256x128 with 64-byte depth stages;
+ *            7, 8, 9: direct-to-LDS 256x128 / 128x128 / 64x64 tiles with 128-byte stages where the depth allows;
+ *            an instance that cannot serve a shape falls back to the next simpler one)
  *   variant  index into that op's variant table, or -1 to restore shape-based selection.
  * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
  * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).

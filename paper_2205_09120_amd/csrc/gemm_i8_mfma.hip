@@ -119,15 +119,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 b_pre[p][j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * ldb);
         }
     };
+    // clamped: the loads only (addresses forced into range); what lies out of range is replaced by zero when the
+    // step is committed, so that no load is followed by a use that would make the wave wait for it at once
     auto fetch_clamped = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
             const int r = m0 + (u >> 2), k = k0 + (u & 3) * 16;
-            const bool ok = r < M && k + 16 <= K;
             const int rr = r < M ? r : M - 1, kk = k + 16 <= K ? k : K - 16;
-            const uint4 v = *reinterpret_cast<const uint4 *>(A + (int64_t)rr * lda + kk);
-            a_pre[p] = make_uint4(ok ? v.x : FLIP, ok ? v.y : FLIP, ok ? v.z : FLIP, ok ? v.w : FLIP);
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)rr * lda + kk);
+            a_pre[p] = make_uint4(src[0], src[1], src[2], src[3]);
         }
 #pragma unroll
         for (int p = 0; p < B_PT; ++p) {
@@ -139,9 +140,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             for (int j = 0; j < 16; ++j) {
                 const int k = k0 + kb * 16 + j;
                 const int kk = k < K ? k : K - 1;
-                const uint32_t x = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
-                b_pre[p][j] = (k < K && n + 4 <= N) ? x : FLIP;
+                b_pre[p][j] = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
             }
+        }
+    };
+    auto mask_clamped = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < A_PT; ++p) {
+            const int u = tid + p * 256;
+            const int r = m0 + (u >> 2), k = k0 + (u & 3) * 16;
+            if (!(r < M && k + 16 <= K))
+                a_pre[p] = make_uint4(FLIP, FLIP, FLIP, FLIP);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PT; ++p) {
+            const int u = (B_UNITS % 256 == 0) ? tid + p * 256 : (tid + p * 256) % B_UNITS;
+            const int kb = u / NQ, nq = u % NQ;
+            const bool n_ok = n0 + nq * 4 + 4 <= N;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                b_pre[p][j] = (n_ok && k0 + kb * 16 + j < K) ? b_pre[p][j] : FLIP;
         }
     };
     auto fetch_bytes = [&](int k0) __attribute__((always_inline)) {
@@ -191,8 +209,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         for (int i = 0; i < 4; ++i)
             cs_acc[p][i] = 0;
 
-    auto commit = [&](int buf) __attribute__((always_inline)) {
+    auto commit = [&](int buf, int k0) __attribute__((always_inline)) {
         uint8_t *As = smem[buf], *Bs = smem[buf] + A_BYTES;
+        if constexpr (MODE == 1)
+            mask_clamped(k0);
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
@@ -259,14 +279,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     // are in flight; they are written to the other buffer afterwards.  One barrier per step.
     const int nsteps = (K + BK - 1) / BK;
     fetch(0);
-    commit(0);
+    commit(0, 0);
     __syncthreads();
     for (int s = 0; s < nsteps; ++s) {
         if (s + 1 < nsteps)
             fetch((s + 1) * BK);
         compute(s & 1);
         if (s + 1 < nsteps)
-            commit((s + 1) & 1);
+            commit((s + 1) & 1, (s + 1) * BK);
         __syncthreads();
     }
 
@@ -394,22 +414,27 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
                     const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)r * lda + k);
                     dst[p] = make_uint4(src[0], src[1], src[2], src[3]);
                 } else {
-                    const bool ok = r < M && k + 16 <= K;
+                    // out-of-range pieces are replaced by zero at commit time, not here: a use right behind the
+                    // load would make the wave wait for it at once
                     const int rr = r < M ? r : M - 1, kk = k + 16 <= K ? k : K - 16;
                     const uint32_t *src = reinterpret_cast<const uint32_t *>(A + (int64_t)rr * lda + kk);
-                    dst[p] = make_uint4(ok ? src[0] : FLIP, ok ? src[1] : FLIP, ok ? src[2] : FLIP, ok ? src[3] : FLIP);
+                    dst[p] = make_uint4(src[0], src[1], src[2], src[3]);
                 }
             }
         };
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             load(pre[d], d);
-        auto commit = [&](const uint4(&src)[A_PT], int buf) __attribute__((always_inline)) {
-            uint8_t *As = smem[buf];
+        auto commit = [&](const uint4(&src)[A_PT], int step) __attribute__((always_inline)) {
+            uint8_t *As = smem[step & 1];
 #pragma unroll
             for (int p = 0; p < A_PT; ++p) {
                 const int u = t + p * 128;
-                const uint4 v = src[p];
+                uint4 v = src[p];
+                if constexpr (MODE == 1) {
+                    if (!(m0 + (u >> 2) < M && step * BK + (u & 3) * 16 + 16 <= K))
+                        v = make_uint4(FLIP, FLIP, FLIP, FLIP);
+                }
                 *reinterpret_cast<uint4 *>(&As[(u >> 2) * A_STRIDE + (u & 3) * 16]) =
                     make_uint4(v.x ^ FLIP, v.y ^ FLIP, v.z ^ FLIP, v.w ^ FLIP);
                 if constexpr (U8)
@@ -423,7 +448,7 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
         for (; s0 < full; s0 += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                commit(pre[d], (s0 + d) & 1);
+                commit(pre[d], s0 + d);
                 load(pre[d], s0 + d + DEPTH);
                 lds_barrier();
             }
@@ -431,7 +456,7 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 #pragma unroll
         for (int d = 0; d + 1 < DEPTH; ++d)
             if (s0 + d < nsteps) {
-                commit(pre[d], (s0 + d) & 1);
+                commit(pre[d], s0 + d);
                 lds_barrier();
             }
         if constexpr (U8) {
@@ -462,20 +487,30 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
                 for (int j = 0; j < 16; ++j) {
                     const int k = k0 + j;
                     const int kk = k < K ? k : K - 1;
-                    const uint32_t x = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);
-                    dst[j] = (k < K && n + 4 <= N) ? x : FLIP;
+                    dst[j] = *reinterpret_cast<const uint32_t *>(B + (int64_t)kk * ldb + nn);  // masked at commit
                 }
             }
         };
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d)
             load(pre[d], d);
-        auto commit = [&](const uint32_t(&src)[16], int buf) __attribute__((always_inline)) {
-            uint8_t *Bs = smem[buf] + A_BYTES;
+        auto commit = [&](const uint32_t(&src)[16], int step) __attribute__((always_inline)) {
+            uint8_t *Bs = smem[step & 1] + A_BYTES;
             uint32_t o[4][4];  // o[q][i]: depth quad q, column i
+            if constexpr (MODE == 1) {
+                uint32_t m[16];
+                const bool n_ok = n0 + nq * 4 + 4 <= N;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                transpose4x4(&src[q * 4], o[q]);
+                for (int j = 0; j < 16; ++j)
+                    m[j] = (n_ok && step * BK + kb * 16 + j < K) ? src[j] : FLIP;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    transpose4x4(&m[q * 4], o[q]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    transpose4x4(&src[q * 4], o[q]);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 *reinterpret_cast<uint4 *>(&Bs[kb * B_BLOCK + i * B_PLANE + nq * 16]) =
@@ -489,7 +524,7 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
         for (; s0 < full; s0 += DEPTH) {
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                commit(pre[d], (s0 + d) & 1);
+                commit(pre[d], s0 + d);
                 load(pre[d], s0 + d + DEPTH);
                 lds_barrier();
             }
@@ -497,7 +532,7 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 #pragma unroll
         for (int d = 0; d + 1 < DEPTH; ++d)
             if (s0 + d < nsteps) {
-                commit(pre[d], (s0 + d) & 1);
+                commit(pre[d], s0 + d);
                 lds_barrier();
             }
         if constexpr (U8) {
@@ -965,30 +1000,39 @@ hipError_t launch_dl(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t l
     return hipGetLastError();
 }
 
-// Shape-based choice among the direct-to-LDS instances (thresholds from sweeps over conv-shaped problems): 256 x 128
-// tiles from half a machine of them up, otherwise 128 x 128 from about 112 tiles up, otherwise 64 x 64 (small
-// problems are latency-bound: more, smaller workgroups win); depth stages of 128 bytes when the depth allows, else 64.
+// One tile shape of the direct-to-LDS kernel: depth stages of 128 bytes when the depth allows, else 64; the 256 x 128
+// tile has an instance without edge handling for whole tiles.
+template <bool U8, int TM, int TN>
+hipError_t launch_dl_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                          int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
+{
+    const bool whole = TM == 4 && (M % (64 * TM)) == 0 && (N % (64 * TN)) == 0;
+    if (K % 128 == 0)
+        return whole ? launch_dl<3, 128, U8, TM, TN, TM != 4>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB)
+                     : launch_dl<3, 128, U8, TM, TN, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+    return whole ? launch_dl<4, 64, U8, TM, TN, TM != 4>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB)
+                 : launch_dl<4, 64, U8, TM, TN, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+}
+
+// Shape-based choice among the direct-to-LDS instances.  A tile shape is eligible if it yields enough workgroups
+// (256 x 128: half a machine of them; 128 x 128: about 112; 64 x 64: always - small problems are latency-bound and more,
+// smaller workgroups win); among the eligible ones the cheapest wins, cost = multiply-adds including those of the
+// padding rows and columns of ragged tiles, divided by the rate the shape reaches on large problems relative to
+// 256 x 128 (measured: 0.8 and 0.47).  Thresholds and rates come from sweeps over conv-shaped problems.
 template <bool U8>
 hipError_t launch_dl_auto(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
 {
-    const int64_t t256 = ((M + 255) / 256) * ((N + 127) / 128);
-    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128);
-    const bool whole256 = (M % 256) == 0 && (N % 128) == 0;
-    if (K % 128 == 0) {
-        if (t256 >= 128)
-            return whole256 ? launch_dl<3, 128, U8, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB)
-                            : launch_dl<3, 128, U8, 4, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
-        if (t128 >= 112)
-            return launch_dl<3, 128, U8, 2, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
-        return launch_dl<3, 128, U8, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
-    }
-    if (K % 64 == 0) {
-        if (t256 >= 128 && whole256)
-            return launch_dl<4, 64, U8, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
-        return launch_dl<4, 64, U8, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
-    }
-    return hipErrorNotSupported;
+    const int64_t m256 = (M + 255) / 256, m128 = (M + 127) / 128, m64 = (M + 63) / 64;
+    const int64_t n128 = (N + 127) / 128, n64 = (N + 63) / 64;
+    const double c256 = m256 * n128 >= 128 ? (double)(m256 * 256) * (double)(n128 * 128) : 1e300;
+    const double c128 = m128 * n128 >= 112 ? (double)(m128 * 128) * (double)(n128 * 128) / 0.8 : 1e300;
+    const double c64 = (double)(m64 * 64) * (double)(n64 * 64) / 0.47;
+    if (c256 <= c128 && c256 <= c64)
+        return launch_dl_tile<U8, 4, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+    if (c128 <= c64)
+        return launch_dl_tile<U8, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
+    return launch_dl_tile<U8, 1, 1>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
 }
 
 int g_i8_forced = -1;
@@ -1013,10 +1057,10 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
         t = tiles >= 128 ? 3 : 0;
     }
     if (t >= 6) {
-        const hipError_t e = t == 6   ? launch_dl<4, 64, false, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
-                             : t == 7 ? launch_dl<3, 128, false, 4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
-                             : t == 8 ? launch_dl<3, 128, false, 2, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
-                                      : launch_dl<3, 128, false, 1, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+        const hipError_t e = t == 6   ? launch_dl<4, 64, false, 4, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                             : t == 7 ? launch_dl_tile<false, 4, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                             : t == 8 ? launch_dl_tile<false, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0)
+                                      : launch_dl_tile<false, 1, 1>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
         if (e != hipErrorNotSupported)
             return e;
         t = 3;

@@ -107,7 +107,8 @@ hipError_t launch_gemm_i8_skinny(int64_t M, int64_t N, int64_t K, const int8_t *
                                  int64_t ldb, int32_t *C, int64_t ldc, hipStream_t stream);
 void i8_force_tile(int t);  // -1 = shape-based, 0 = 128x128, 1 = 256x256, 2 = 256x128 (4 waves each),
                             // 3 / 4 / 5 = wave-specialised 256x128 with 3 / 2 / 4 depth steps of prefetch,
-                            // 6 / 7 = direct-to-LDS 256x128 with 4 stages of 64 / 3 stages of 128 depth bytes,
-                            // 8 / 9 = direct-to-LDS 128x128 / 64x64 (ragged extents allowed), 128-byte stages
+                            // 6 = direct-to-LDS 256x128 with 4 stages of 64 depth bytes, 7 / 8 / 9 = direct-to-LDS
+                            // 256x128 / 128x128 / 64x64 with 3 stages of 128 depth bytes (4 of 64 if the depth is
+                            // not a multiple of 128); ragged extents allowed
 
 }  // namespace lowbit
