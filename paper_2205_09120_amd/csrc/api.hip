@@ -77,18 +77,24 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
     return LB_OK;
 }
 
-// Pick a tile variant: the highest-ranked one that still yields enough workgroups to occupy the 256 compute
-// units eight times over; problems too small for that take the variant with the most workgroups.
-int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV)
+// Pick a tile variant.  Problems of a few hundred 16 x 64 tiles are latency-bound and take the first matching
+// small-problem instance of the table; otherwise the highest-ranked variant that still yields enough workgroups
+// (six per compute unit for the 32 x 64 tile of rank 2, eight for the larger tiles), and failing that the ranked
+// variant with the most workgroups.
+int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV, int64_t KW)
 {
-    constexpr int64_t kWanted = 256 * 8;
+    const int64_t n16 = ((rowsS + 15) / 16) * ((rowsV + 63) / 64);
+    for (int i = 0; i < count; ++i)
+        if (tab[i].small_max > 0 && n16 <= tab[i].small_max && KW >= tab[i].small_min_kw)
+            return i;
     int best = -1, fallback = 0;
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
         if (tab[i].rank <= 0)
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
-        if (wg >= kWanted && (best < 0 || tab[i].rank > tab[best].rank))
+        const int64_t wanted = tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
+        if (wg >= wanted && (best < 0 || tab[i].rank > tab[best].rank))
             best = i;
         if (wg > fallback_wg) {
             fallback_wg = wg;
@@ -188,7 +194,7 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     a.ldc = ldc;
     a.c16 = c16 ? 1 : 0;
     a.stream = static_cast<hipStream_t>(stream);
-    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV);
+    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
     const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -443,7 +449,7 @@ int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t K, cons
     a.q_out = Out;
     a.q_planes = out_planes;
     const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
-    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV);
+    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
     const hipError_t e = tab[v].launch_transposed(a);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));

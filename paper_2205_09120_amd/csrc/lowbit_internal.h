@@ -34,6 +34,8 @@ struct GemmVariant {
     int tileS, tileV;  // workgroup tile extents along S and V
     hipError_t (*launch)(const GemmArgs &);
     hipError_t (*launch_transposed)(const GemmArgs &);
+    int small_max;     // > 0: chosen for problems of at most this many 16 x 64 tiles (first match in table order) ...
+    int small_min_kw;  // ... whose depth is at least this many 64-bit words
 };
 
 const GemmVariant *gemm_variants(int kind, int *count);
