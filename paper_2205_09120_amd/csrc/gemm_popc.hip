@@ -505,8 +505,9 @@ hipError_t launch(const GemmArgs &a)
 // workgroups, otherwise the ranked variant with the most workgroups; 0 = only reachable through lb_set_variant).
 // The first row of each table is the small-problem instance: 4 x 64 outputs per wave and scalar loads of 16 dwords.
 // The LB_SMALL rows serve problems of a few hundred tiles, which are bound by the latency of their few dependent
-// memory round trips rather than by throughput: 2 x 64 outputs per wave and / or 8 waves per workgroup put more
-// waves on every SIMD to overlap those round trips (measured 1.05-1.35x over the first row on such shapes).
+// memory round trips rather than by throughput: 1 or 2 strings per wave and 8 waves per workgroup put more waves
+// on every SIMD to overlap those round trips (measured 1.05-1.6x over the first row on such shapes; the limits
+// come from a sweep over 64..512 x 64..3136 x 256..2304).  A row may repeat an instance with another condition.
 const GemmVariant kBnn[] = {
     LB_VARIANT(1, KIND_BNN, 4, 1, 4, 16, 8),
     LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 4),
@@ -515,7 +516,8 @@ const GemmVariant kBnn[] = {
     LB_VARIANT(3, KIND_BNN, 8, 2, 4, 8, 4),
     LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8, 2),
     LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
-    LB_SMALL(160, 0, KIND_BNN, 2, 1, 4, 16, 8),
+    LB_SMALL(64, 0, KIND_BNN, 1, 1, 4, 16, 8),
+    LB_SMALL(160, 0, KIND_BNN, 1, 1, 8, 16, 8),
     LB_SMALL(600, 0, KIND_BNN, 2, 1, 8, 16, 8),
     LB_SMALL(1200, 0, KIND_BNN, 4, 1, 8, 16, 8),
 };
@@ -527,7 +529,7 @@ const GemmVariant kTnn[] = {
     LB_VARIANT(0, KIND_TNN, 8, 4, 4, 4, 1),
     LB_VARIANT(0, KIND_TNN, 8, 4, 4, 2, 1),
     LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4, 2),
-    LB_SMALL(160, 0, KIND_TNN, 2, 1, 4, 16, 4),
+    LB_SMALL(300, 0, KIND_TNN, 1, 1, 8, 16, 4),
     LB_SMALL(600, 0, KIND_TNN, 2, 1, 8, 16, 4),
     LB_SMALL(1200, 0, KIND_TNN, 4, 1, 8, 16, 4),
 };
@@ -538,9 +540,10 @@ const GemmVariant kTbn[] = {
     LB_VARIANT(4, KIND_TBN, 8, 4, 8, 4, 1),
     LB_VARIANT(0, KIND_TBN, 8, 4, 4, 4, 4),
     LB_VARIANT(0, KIND_TBN, 8, 2, 4, 8, 4),
-    LB_SMALL(160, 0, KIND_TBN, 2, 1, 4, 16, 8),
-    LB_SMALL(300, 24, KIND_TBN, 2, 1, 8, 16, 8),
-    LB_SMALL(1800, 24, KIND_TBN, 4, 1, 8, 16, 8),
+    LB_SMALL(64, 0, KIND_TBN, 1, 1, 4, 16, 8),
+    LB_SMALL(160, 0, KIND_TBN, 1, 1, 8, 16, 8),
+    LB_SMALL(300, 18, KIND_TBN, 1, 1, 8, 16, 8),
+    LB_SMALL(1800, 18, KIND_TBN, 4, 1, 8, 16, 8),
 };
 
 }  // namespace
