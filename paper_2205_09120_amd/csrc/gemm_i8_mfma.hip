@@ -99,7 +99,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     //   0 raw      M, N, K multiples of the tile and aligned operands: no checks
     //   1 clamped  aligned operands with N % 4 == 0 and K % 16 == 0: addresses are clamped into range and
     //              out-of-range pieces replaced by zero
-    //   2 bytes    anything else: guarded byte loads (slow, rare)
+    //   2 overlap  any alignment and any M, N >= 4, K >= 64: the last depth step starts at K - 64 and the depth
+    //              positions it shares with the step before are zeroed in A; a column quad that sticks out over N is
+    //              fetched from N - 4 and stored to the columns it really holds; loads go through memcpy, which the
+    //              compiler turns into dword / dwordx4 loads that need no alignment
+    //   3 bytes    N < 4 or K < 64: guarded byte loads (slow, tiny problems only)
     auto fetch_raw = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
@@ -162,6 +166,58 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 b_pre[p][j] = (n_ok && k0 + kb * 16 + j < K) ? b_pre[p][j] : FLIP;
         }
     };
+    const int nsteps = (K + BK - 1) / BK;
+    // first depth position of step s (mode 2: the last step is shifted back so that it ends at K)
+    auto kstart = [&](int s) { return (MODE == 2 && s == nsteps - 1) ? K - BK : s * BK; };
+    auto fetch_overlap = [&](int k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < A_PT; ++p) {
+            const int u = tid + p * 256;
+            const int r = m0 + (u >> 2);
+            const int rr = r < M ? r : M - 1;
+            __builtin_memcpy(&a_pre[p], A + (int64_t)rr * lda + k0 + (u & 3) * 16, 16);
+        }
+#pragma unroll
+        for (int p = 0; p < B_PT; ++p) {
+            const int u = (B_UNITS % 256 == 0) ? tid + p * 256 : (tid + p * 256) % B_UNITS;
+            const int kb = u / NQ, nq = u % NQ;
+            const int n = n0 + nq * 4;
+            const int nn = n + 4 <= N ? n : N - 4;
+            const int8_t *src = B + (int64_t)(k0 + kb * 16) * ldb + nn;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                __builtin_memcpy(&b_pre[p][j], src + (int64_t)j * ldb, 4);
+        }
+    };
+    // last step of mode 2: its first `cut` depth positions were already multiplied by the step before
+    auto mask_overlap = [&](int s) __attribute__((always_inline)) {
+        const int cut = s == nsteps - 1 ? (nsteps - 1) * BK - (K - BK) : 0;
+        if (cut <= 0)
+            return;
+#pragma unroll
+        for (int p = 0; p < A_PT; ++p) {
+            const int u = tid + p * 256;
+            const int z = cut - (u & 3) * 16;  // leading bytes of this 16-byte piece to zero
+            uint32_t w[4] = {a_pre[p].x, a_pre[p].y, a_pre[p].z, a_pre[p].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int nz = z - 4 * j;
+                const uint32_t m = nz >= 4 ? 0xffffffffu : nz <= 0 ? 0u : ((1u << (8 * nz)) - 1u);
+                w[j] = (w[j] & ~m) | (FLIP & m);
+            }
+            a_pre[p] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        if constexpr (U8) {  // the column sums must not count those rows twice either
+#pragma unroll
+            for (int p = 0; p < B_PT; ++p) {
+                const int u = (B_UNITS % 256 == 0) ? tid + p * 256 : (tid + p * 256) % B_UNITS;
+                const int kb = u / NQ;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    b_pre[p][j] = kb * 16 + j < cut ? FLIP : b_pre[p][j];
+            }
+        }
+    };
     auto fetch_bytes = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
@@ -193,6 +249,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
             fetch_raw(k0);
         else if constexpr (MODE == 1)
             fetch_clamped(k0);
+        else if constexpr (MODE == 2)
+            fetch_overlap(k0);
         else
             fetch_bytes(k0);
     };
@@ -209,10 +267,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
         for (int i = 0; i < 4; ++i)
             cs_acc[p][i] = 0;
 
-    auto commit = [&](int buf, int k0) __attribute__((always_inline)) {
+    auto commit = [&](int s) __attribute__((always_inline)) {
+        const int buf = s & 1;
         uint8_t *As = smem[buf], *Bs = smem[buf] + A_BYTES;
         if constexpr (MODE == 1)
-            mask_clamped(k0);
+            mask_clamped(s * BK);
+        if constexpr (MODE == 2)
+            mask_overlap(s);
 #pragma unroll
         for (int p = 0; p < A_PT; ++p) {
             const int u = tid + p * 256;
@@ -277,16 +338,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 
     // Software pipeline over depth steps: while step s is multiplied out of LDS buffer s%2 the loads of step s+1
     // are in flight; they are written to the other buffer afterwards.  One barrier per step.
-    const int nsteps = (K + BK - 1) / BK;
-    fetch(0);
-    commit(0, 0);
+    fetch(kstart(0));
+    commit(0);
     __syncthreads();
     for (int s = 0; s < nsteps; ++s) {
         if (s + 1 < nsteps)
-            fetch((s + 1) * BK);
+            fetch(kstart(s + 1));
         compute(s & 1);
         if (s + 1 < nsteps)
-            commit((s + 1) & 1, (s + 1) * BK);
+            commit(s + 1);
         __syncthreads();
     }
 
@@ -318,7 +378,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int lcol = (wn * TN + j) * 32 + (lane & 31);
-            const int col = n0 + lcol;
+            int col = n0 + lcol;
+            bool col_ok = col < N;
+            if constexpr (MODE == 2) {
+                // a quad that sticks out over N was fetched from column N - 4: its slots hold columns N-4 .. N-1;
+                // those below the quad's own first column belong to the quad before and are not stored again
+                const int nq0 = n0 + (lcol & ~3);
+                if (nq0 + 4 > N) {
+                    col = N - 4 + (lcol & 3);
+                    col_ok = nq0 < N && col >= nq0;
+                }
+            }
             int32_t ccorr = 0;
             if constexpr (U8)
                 ccorr = K * zA * zB - zA * (csum[lcol * 4] + csum[lcol * 4 + 1] + csum[lcol * 4 + 2] + csum[lcol * 4 + 3]);
@@ -329,7 +399,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                 int32_t out = acc[i][j][r];
                 if constexpr (U8)
                     out += ccorr - zB * (rsum[lrow * 4] + rsum[lrow * 4 + 1] + rsum[lrow * 4 + 2] + rsum[lrow * 4 + 3]);
-                if (row < M && col < N)
+                if (row < M && col_ok)
                     C[(int64_t)row * ldc + col] = out;
             }
         }
@@ -605,7 +675,17 @@ __global__ __launch_bounds__(512) void gemm_i8_ws_kernel(int M, int N, int K, co
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int lcol = (wn * TN + j) * 32 + (lane & 31);
-            const int col = n0 + lcol;
+            int col = n0 + lcol;
+            bool col_ok = col < N;
+            if constexpr (MODE == 2) {
+                // a quad that sticks out over N was fetched from column N - 4: its slots hold columns N-4 .. N-1;
+                // those below the quad's own first column belong to the quad before and are not stored again
+                const int nq0 = n0 + (lcol & ~3);
+                if (nq0 + 4 > N) {
+                    col = N - 4 + (lcol & 3);
+                    col_ok = nq0 < N && col >= nq0;
+                }
+            }
             int32_t ccorr = 0;
             if constexpr (U8)
                 ccorr = K * zA * zB - zA * (csum[lcol * 4] + csum[lcol * 4 + 1] + csum[lcol * 4 + 2] + csum[lcol * 4 + 3]);
@@ -942,8 +1022,11 @@ hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t
     else if (aligned && can_clamp)
         hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 1, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
                            ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
-    else
+    else if (N >= 4 && K >= BK)
         hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 2, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
+                           ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
+    else
+        hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 3, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
                            ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     return hipGetLastError();
 }
@@ -1077,6 +1160,9 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
         return launch_tile<4, 4, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     if (t == 2)
         return launch_tile<4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
+    // unforced small problems: 64 x 64 tiles put four times as many workgroups on the machine
+    if (g_i8_forced < 0 && ((M + 127) / 128) * ((N + 127) / 128) < 128)
+        return launch_tile<1, 1, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     return launch_tile<2, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
 }
 
@@ -1095,6 +1181,8 @@ hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int
             return e;
         return launch_tile<4, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
     }
+    if (((M + 127) / 128) * ((N + 127) / 128) < 128)
+        return launch_tile<1, 1, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
     return launch_tile<2, 2, true>(M, N, K, a, lda, b, ldb, C, ldc, stream, zA - 128, zB - 128);
 }
 
