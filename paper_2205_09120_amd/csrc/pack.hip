@@ -11,7 +11,9 @@
 //     bit of each byte into four per-byte shift registers (8 depth positions per byte), transposes the bytes in
 //     registers, and the workgroup writes its 128 strings x 8 words tile through LDS so that stores are
 //     contiguous along the depth words.
-//   * anything else (odd strides, misaligned pointers): one thread per output word, byte loads.
+// Source loads go through memcpy, which the compiler lowers to the same dword / dwordx4 loads for any address:
+// global memory needs no alignment for them, so odd leading dimensions and misaligned pointers take the same
+// kernels (a leading dimension of 4600 instead of 4608 costs a few percent, not the 9x of byte loads).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -51,7 +53,6 @@ template <int Q> __device__ __forceinline__ uint32_t quad_bcast(uint32_t x)
 
 // ---------------------------------------------------------------------------------------------------------
 // depth-contiguous source.  Thread t handles bytes [16*(t%4), +16) of word (t/4) in row-major (r, w) order.
-// Requires stride_r % 16 == 0 and a 16-byte aligned src.
 template <bool TERNARY>
 __global__ __launch_bounds__(256) void pack_kcontig_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
                                                            int64_t KW, int64_t stride_r, uint32_t *__restrict__ dst)
@@ -66,7 +67,15 @@ __global__ __launch_bounds__(256) void pack_kcontig_kernel(const int8_t *__restr
         const int64_t k0 = w * 64 + q * 16;
         const int8_t *p = src + r * stride_r + k0;
         if (k0 + 16 <= K) {
-            v = *reinterpret_cast<const uint4 *>(p);
+            __builtin_memcpy(&v, p, 16);
+        } else if (k0 < K && K >= 16) {
+            // last piece of a row: fetch the 16 bytes that end at K and shift the ones before k0 out
+            uint64_t h[2];
+            __builtin_memcpy(h, src + r * stride_r + (K - 16), 16);
+            const int sb = 8 * (int)(k0 + 16 - K);  // 8 .. 120 bits
+            const uint64_t lo = sb >= 64 ? h[1] >> (sb - 64) : (h[0] >> sb) | (h[1] << (64 - sb));
+            const uint64_t hi = sb >= 64 ? 0 : h[1] >> sb;
+            v = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
         } else if (k0 < K) {
             uint32_t tmp[4] = {0u, 0u, 0u, 0u};
             for (int i = 0; i < (int)(K - k0); ++i)
@@ -101,7 +110,6 @@ __global__ __launch_bounds__(256) void pack_kcontig_kernel(const int8_t *__restr
 
 // ---------------------------------------------------------------------------------------------------------
 // depth-strided source.  Workgroup tile: 128 bit strings x 8 depth words.  Thread (quad = tid%32, w = tid/32).
-// Requires stride_k % 4 == 0 and a 4-byte aligned src.
 template <bool TERNARY>
 __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
                                                             int64_t KW, int64_t stride_k, uint32_t *__restrict__ dst,
@@ -127,7 +135,7 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
             uint32_t x[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                x[j] = *reinterpret_cast<const uint32_t *>(p);
+                __builtin_memcpy(&x[j], p, 4);
                 p += stride_k;
             }
             uint32_t an = 0u, ap = 0u;
@@ -151,7 +159,7 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
                 if (k < K && r0 < rows) {
                     const int8_t *p = src + k * stride_k + r0;
                     if (r0 + 4 <= rows) {
-                        x = *reinterpret_cast<const uint32_t *>(p);
+                        __builtin_memcpy(&x, p, 4);
                     } else {
                         for (int i = 0; i < (int)(rows - r0); ++i)
                             x |= (uint32_t)(uint8_t)p[i] << (8 * i);
@@ -206,33 +214,6 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
     }
 }
 
-// ---------------------------------------------------------------------------------------------------------
-// any strides: one thread per output word
-template <bool TERNARY>
-__global__ __launch_bounds__(256) void pack_generic_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
-                                                           int64_t KW, int64_t stride_r, int64_t stride_k,
-                                                           uint64_t *__restrict__ dst)
-{
-    const int64_t word = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (word >= rows * KW)
-        return;
-    const int64_t r = word / KW, w = word - r * KW;
-    uint64_t plus = 0, minus = 0;
-    const int64_t k0 = w * 64;
-    const int n = (int)((K - k0) < 64 ? (K - k0) : 64);
-    for (int b = 0; b < n; ++b) {
-        const int8_t x = src[r * stride_r + (k0 + b) * stride_k];
-        plus |= (uint64_t)(x > 0) << b;
-        minus |= (uint64_t)(x < 0) << b;
-    }
-    if (TERNARY) {
-        dst[word * 2] = plus;
-        dst[word * 2 + 1] = minus;
-    } else {
-        dst[word] = minus;
-    }
-}
-
 }  // namespace
 
 hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
@@ -242,9 +223,9 @@ hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K,
     const int64_t words = rows * KW;
     if (words == 0)
         return hipSuccess;
-    const uintptr_t sa = reinterpret_cast<uintptr_t>(src);
     uint32_t *d32 = reinterpret_cast<uint32_t *>(dst);
-    if (stride_k == 1 && (stride_r % 16) == 0 && (sa % 16) == 0) {
+    // the C ABI admits exactly two layouts: depth-contiguous (stride_k == 1) and depth-strided (stride_r == 1)
+    if (stride_k == 1) {
         const int64_t blocks = (words * 4 + 255) / 256;
         if (blocks > 0x7fffffffLL)
             return hipErrorInvalidConfiguration;
@@ -254,7 +235,7 @@ hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K,
         else
             hipLaunchKernelGGL(pack_kcontig_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
                                KW, stride_r, d32);
-    } else if (stride_r == 1 && (stride_k % 4) == 0 && (sa % 4) == 0) {
+    } else if (stride_r == 1) {
         const int64_t nRB = (rows + 127) / 128, nWB = (KW + 7) / 8;
         const int64_t blocks = nRB * nWB;
         if (blocks > 0x7fffffffLL)
@@ -266,15 +247,7 @@ hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K,
             hipLaunchKernelGGL(pack_kstrided_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
                                KW, stride_k, d32, nRB);
     } else {
-        const int64_t blocks = (words + 255) / 256;
-        if (blocks > 0x7fffffffLL)
-            return hipErrorInvalidConfiguration;
-        if (ternary)
-            hipLaunchKernelGGL(pack_generic_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
-                               KW, stride_r, stride_k, dst);
-        else
-            hipLaunchKernelGGL(pack_generic_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, stream, src, rows, K,
-                               KW, stride_r, stride_k, dst);
+        return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
