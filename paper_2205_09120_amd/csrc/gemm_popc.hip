@@ -375,11 +375,13 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                     int16_t *crow = C16 + (int64_t)v * ldc + s0;
                     bool done = false;
                     if constexpr (TS % 4 == 0) {
-                        if (s0 + TS <= rowsS && ((reinterpret_cast<uintptr_t>(crow) & 7) == 0)) {
+                        if (s0 + TS <= rowsS) {
 #pragma unroll
-                            for (int i = 0; i < TS; i += 4)
-                                *reinterpret_cast<int2 *>(crow + i) =
-                                    make_int2((out[i] & 0xffff) | (out[i + 1] << 16), (out[i + 2] & 0xffff) | (out[i + 3] << 16));
+                            for (int i = 0; i < TS; i += 4) {
+                                const int2 q = make_int2((out[i] & 0xffff) | (out[i + 1] << 16),
+                                                         (out[i + 2] & 0xffff) | (out[i + 3] << 16));
+                                __builtin_memcpy(crow + i, &q, 8);  // no 8-byte alignment needed
+                            }
                             done = true;
                         }
                     }
@@ -400,10 +402,13 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             } else {
                 int32_t *crow = C + (int64_t)v * ldc + s0;
                 if constexpr (TS % 4 == 0) {
-                    if (s0 + TS <= rowsS && ((reinterpret_cast<uintptr_t>(crow) & 15) == 0)) {
+                    if (s0 + TS <= rowsS) {
+                        // 128-bit stores through memcpy: they need no 16-byte alignment (odd ldc, odd N)
 #pragma unroll
-                        for (int i = 0; i < TS; i += 4)
-                            *reinterpret_cast<int4 *>(crow + i) = make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);
+                        for (int i = 0; i < TS; i += 4) {
+                            const int4 q = make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);
+                            __builtin_memcpy(crow + i, &q, 16);
+                        }
                         continue;
                     }
                 }
