@@ -80,17 +80,19 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
 // Pick a tile variant.  Problems of a few hundred 16 x 64 tiles are latency-bound and take the first matching
 // small-problem instance of the table; otherwise the highest-ranked variant that still yields enough workgroups
 // (six per compute unit for the 32 x 64 tile of rank 2, eight for the larger tiles), and failing that the ranked
-// variant with the most workgroups.
+// variant with the most workgroups.  A scalar side of at most 8 (16) strings only admits tiles of at most 8 (16)
+// rows, so that no wave multiplies padding.
 int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV, int64_t KW)
 {
+    const int max_tile_s = rowsS <= 8 ? 8 : rowsS <= 16 ? 16 : 1 << 30;
     const int64_t n16 = ((rowsS + 15) / 16) * ((rowsV + 63) / 64);
     for (int i = 0; i < count; ++i)
-        if (tab[i].small_max > 0 && n16 <= tab[i].small_max && KW >= tab[i].small_min_kw)
+        if (tab[i].small_max > 0 && tab[i].tileS <= max_tile_s && n16 <= tab[i].small_max && KW >= tab[i].small_min_kw)
             return i;
-    int best = -1, fallback = 0;
+    int best = -1, fallback = -1;
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
-        if (tab[i].rank <= 0)
+        if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s)
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
         const int64_t wanted = tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
@@ -101,7 +103,19 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
             fallback = i;
         }
     }
-    return best >= 0 ? best : fallback;
+    if (best >= 0)
+        return best;
+    if (fallback >= 0)
+        return fallback;
+    // no ranked variant is low enough: the tallest 64-column instance that is
+    int fit = 0;
+    bool found = false;
+    for (int i = 0; i < count; ++i)
+        if (tab[i].tileV == 64 && tab[i].tileS <= max_tile_s && (!found || tab[i].tileS > tab[fit].tileS)) {
+            fit = i;
+            found = true;
+        }
+    return fit;
 }
 
 // Argument rules common to gemm_bnn / gemm_tnn / gemm_tbn and to every problem of a grouped launch.
@@ -133,6 +147,19 @@ int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t
     return LB_OK;
 }
 
+// Depth-split (skinny) kernel or tiled kernel for a product with at most 16 strings on one side?  The skinny kernel
+// streams the `rows` long strings once per 8 short ones and pays a cross-lane reduction per row, so it wins when the
+// depth is large against the row count; the tiled kernel wins on many shallow rows (measured over rows 1 K .. 256 K,
+// depth 1 K .. 64 K, 1 / 8 / 16 short strings: up to 10x either way).
+bool prefer_skinny(int64_t rows, int64_t narrow, int64_t K)
+{
+    if (K < 2048)
+        return false;
+    if (narrow <= 8)
+        return K >= 16384 || rows <= K;
+    return rows <= (K < 16384 ? K : 16384);
+}
+
 // Which operand rides in scalar registers.  TBN: always the binary one (one scalar source per instruction), so lanes
 // own rows of C.  BNN / TNN: lanes own columns of C (coalesced stores) unless N is too narrow to fill a wavefront and
 // M is not.
@@ -155,8 +182,10 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     // Skinny problems (fully connected layers with a small batch) stream the large operand once and split the
     // depth across lanes.  A forced tile variant bypasses this path.
     if (!forced) {
-        const bool skinny_n = N <= kSkinnyMax && M >= 64;
-        const bool skinny_m = !skinny_n && M <= kSkinnyMax && N >= 64 && kind != lowbit::KIND_TBN;
+        const bool narrow_n = N <= kSkinnyMax && M >= 64;
+        const bool narrow_m = !narrow_n && M <= kSkinnyMax && N >= 64 && kind != lowbit::KIND_TBN;
+        const bool skinny_n = narrow_n && prefer_skinny(M, N, K);
+        const bool skinny_m = narrow_m && prefer_skinny(N, M, K);
         if (skinny_n || skinny_m) {
             lowbit::SkinnyArgs sa;
             sa.Xp = skinny_n ? Ap : Bp;

@@ -244,12 +244,15 @@ int g_skinny_forced = -1;
 
 template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
 {
-    // (rows per wave, waves per workgroup), measured on M x 16384 x 8 problems: large row counts stream best
-    // with 4 rows per wave; a few thousand rows are latency-bound and want many small waves in flight
+    // (rows per wave, waves per workgroup), measured on M x 4096 .. 65536 x 1 .. 16 problems: large row counts
+    // stream best with 2 rows per wave (binary operands, half the bytes per row: 4); a few thousand rows are
+    // latency-bound and want many small waves in flight
     int cfg = g_skinny_forced;
     if (cfg < 0) {
         if (a.rowsX >= 16384)
-            cfg = 0;
+            cfg = KIND == KIND_BNN ? 7 : KIND == KIND_TNN ? 3 : 1;
+        else if (a.rowsX >= 6144)
+            cfg = 3;
         else if (a.rowsX >= 2048)
             cfg = 5;
         else

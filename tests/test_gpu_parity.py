@@ -157,12 +157,18 @@ def test_gemm_edge_shapes_all_variants(kind):
 
 
 SKINNY_SHAPES = [(64, 1, 64), (64, 8, 1), (100, 9, 16384 + 70), (4096, 16, 300), (1000, 3, 20000), (3, 1000, 700),
-                 (16, 64, 16385), (8, 4100, 130), (257, 8, 16384), (5000, 7, 65)]
+                 (16, 64, 16385), (8, 4100, 130), (257, 8, 16384), (5000, 7, 65),
+                 # deep enough for the depth-split kernel (depth >= 2048 and not many more rows than depth) ...
+                 (300, 8, 2048 + 70), (4096, 16, 4100), (2100, 5, 2049), (5, 3000, 4000), (9, 2500, 2304),
+                 (20000, 2, 16384 + 64), (7000, 11, 9000),
+                 # ... and narrow shapes that the tiled kernel serves: many shallow rows, 1 / 8 / 16 strings
+                 (30000, 1, 600), (30000, 8, 1000), (30000, 13, 2500), (20000, 16, 20000 // 8), (12, 30000, 1000)]
 
 
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
 def test_gemm_skinny_shapes(kind):
-    """Shapes with one narrow side take the depth-split kernel (both orientations, several depth chunks, tails)."""
+    """Shapes with one narrow side: the depth-split kernel (both orientations, several depth chunks, tails) where
+    the depth is large against the row count, the tiled kernel with low tiles elsewhere."""
     for (M, N, K) in SKINNY_SHAPES:
         say(f"gemm_{kind} skinny M={M} N={N} K={K}")
         A, B = synth.make_custom(kind, M, N, K, seed=M + 5 * N + 11 * K)
