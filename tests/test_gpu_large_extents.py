@@ -133,3 +133,39 @@ def test_i8_mfma_at_the_depth_limit(K):
     with pytest.raises(lb.LowbitError) as e:
         lb.gemm_i8_mfma(M, N, 131072, torch.from_numpy(A).cuda(), 131072, torch.from_numpy(B).cuda(), N)
     assert e.value.status == lb.LB_EOVERFLOW
+
+
+def test_im2col_packed_more_than_2_pow_31_pieces():
+    """A binary lowering whose output has more than 2^31 eight-byte pieces (64-bit index arithmetic in the kernel):
+    10 maps of 1000 x 1000 x 64, a 15 x 15 window -> 10 M strings of depth 14400 (18 GB).  Sampled output strings,
+    among them the corners, the last one and the ones around piece 2^31, are rebuilt by the im2col oracle from the
+    window of the unpacked map."""
+    from oracle import im2col as im2col_ref
+    nb, H, W, C, k, pad = 10, 1000, 1000, 64, 15, 7
+    taps = k * k
+    assert nb * H * W * taps > 2 ** 31
+    say(f"im2col_packed binary {nb}x{H}x{W}x{C} window {k}x{k}: {nb * H * W * taps} pieces")
+    rng = np.random.default_rng(99)
+    fmap = rng.integers(0, 2, size=(nb, H, W, C), dtype=np.int8)
+    fmap = (fmap * 2 - 1).astype(np.int8)
+    d = torch.from_numpy(fmap).cuda()
+    Fp = lb.pack_binary(d, nb * H * W, C, C, 1)
+    del d
+    Bp = lb.im2col_packed(Fp, 1, nb, H, W, C, k, k, 1, 1, pad, pad)
+    torch.cuda.synchronize()
+    assert Bp.numel() == nb * H * W * taps
+    n_mid = 2 ** 31 // taps
+    pick = np.concatenate([np.array([0, W - 1, (H - 1) * W, H * W - 1, nb * H * W - 1, n_mid - 1, n_mid, n_mid + 1]),
+                           rng.integers(0, nb * H * W, size=600)])
+    got = Bp.view(nb * H * W, taps)[torch.from_numpy(pick).cuda()].cpu().numpy().view(np.uint64)
+    for row, n in zip(got, pick):
+        b, r = divmod(int(n), H * W)
+        oy, ox = divmod(r, W)
+        win = np.zeros((1, k, k, C), dtype=np.int8)                       # the window, zero outside the map
+        y0, y1, x0, x1 = max(oy - pad, 0), min(oy + pad + 1, H), max(ox - pad, 0), min(ox + pad + 1, W)
+        win[0, y0 - (oy - pad):y1 - (oy - pad), x0 - (ox - pad):x1 - (ox - pad), :] = fmap[b, y0:y1, x0:x1, :]
+        col = im2col_ref.im2col(win, k, k)                                # (k*k*C, 1): the string of this pixel
+        # padding positions hold 0 in the unpacked column; the packed binary string has bit 0 there as well
+        want = bitref.pack_binary(np.ascontiguousarray(col.T)).reshape(-1)
+        assert np.array_equal(row, want), int(n)
+    del Bp
