@@ -183,7 +183,7 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     // depth across lanes.  A forced tile variant bypasses this path.
     if (!forced) {
         const bool narrow_n = N <= kSkinnyMax && M >= 64;
-        const bool narrow_m = !narrow_n && M <= kSkinnyMax && N >= 64 && kind != lowbit::KIND_TBN;
+        const bool narrow_m = !narrow_n && M <= kSkinnyMax && N >= 64;
         const bool skinny_n = narrow_n && prefer_skinny(M, N, K);
         const bool skinny_m = narrow_m && prefer_skinny(N, M, K);
         if (skinny_n || skinny_m) {
@@ -198,14 +198,23 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
             sa.ldc = ldc;
             sa.c16 = c16 ? 1 : 0;
             sa.stream = static_cast<hipStream_t>(stream);
-            const hipError_t e = lowbit::launch_gemm_skinny(kind, sa, skinny_m);
+            // gemm_tbn with few ternary rows: the binary operand is the streamed one
+            const int sk_kind = (kind == lowbit::KIND_TBN && skinny_m) ? lowbit::KIND_TBN_SV : kind;
+            const hipError_t e = lowbit::launch_gemm_skinny(sk_kind, sa, skinny_m);
             if (e != hipSuccess)
                 return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
             return LB_OK;
         }
     }
     lowbit::GemmArgs a;
-    const bool transposed = b_on_scalar_side(kind, M, N);
+    // gemm_tbn normally keeps the binary operand on the scalar side (2 instructions per word, lanes own rows of C).
+    // With at most 32 ternary rows most of those lanes would idle: then the ternary operand goes to the scalar side
+    // (3 instructions per word, lanes own columns of C).
+    if (kind == lowbit::KIND_TBN && !forced && M <= 32 && N > M) {
+        kind = lowbit::KIND_TBN_SV;
+        tab = lowbit::gemm_variants(kind, &count);
+    }
+    const bool transposed = kind != lowbit::KIND_TBN_SV && b_on_scalar_side(kind, M, N);
     if (transposed) {
         a.Sp = reinterpret_cast<const uint32_t *>(Bp);
         a.rowsS = (int)N;

@@ -11,6 +11,10 @@
 //        BNN: x = s ^ v;                    acc += popcount(x)                     (2 instructions, eq. (6))
 //        TNN: m = nz_s & nz_v; u = (neg_s ^ neg_v) & m;  M += popcount(m); U += popcount(u)     (4 instructions)
 //        TBN: u = (neg_v ^ y_s) & nz_v;     U += popcount(u)   (+ a per-string popcount(nz_v))  (2 instructions)
+//        TBN with the ternary operand on the scalar side (few ternary strings, so that lanes own binary strings):
+//             t = nz_s & y_v; u = neg_s ^ t;  U += popcount(u)   (3 instructions: only one operand of an
+//             instruction may come from a scalar register, and neg is a subset of nz, so (neg ^ y) & nz = (nz & y) ^ neg;
+//             popcount(nz_s) is counted on the scalar ALU)
 //     where nz = x+ | x- and neg = x-.  With P = popcount(z+), Q = popcount(z-) of eq. (7): M = P + Q and U = Q,
 //     so C = M - 2U (TNN) and C = popcount(nz_v) - 2U (TBN) are the integers eq. (7) defines; the forms need
 //     fewer instructions than evaluating z+ and z- separately because gfx950 has a three-input bit operation.
@@ -37,6 +41,7 @@ template <int KIND> struct Traits;
 template <> struct Traits<KIND_BNN> { static constexpr int SD = 2, VD = 2, ACC = 1; };
 template <> struct Traits<KIND_TNN> { static constexpr int SD = 4, VD = 4, ACC = 2; };
 template <> struct Traits<KIND_TBN> { static constexpr int SD = 2, VD = 4, ACC = 1; };  // S binary, V ternary
+template <> struct Traits<KIND_TBN_SV> { static constexpr int SD = 4, VD = 2, ACC = 1; };  // S ternary, V binary
 
 template <int D> struct Vec;
 template <> struct Vec<2> { using type = uint2; };
@@ -149,6 +154,11 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
     // strings, so counting in the main loop would repeat the work WAVES times; instead each staged element is counted
     // once, by the lane that stages it, and the partial counts meet in LDS after the main loop.
     int32_t nnz_part[UPW];
+    // TBN_SV: non-zero counts of this wave's S strings (the same in every lane)
+    int32_t snnz[TS];
+#pragma unroll
+    for (int i = 0; i < TS; ++i)
+        snnz[i] = 0;
     if constexpr (KIND == KIND_TBN) {
 #pragma unroll
         for (int j = 0; j < UPW; ++j)
@@ -200,11 +210,13 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             for (int i = 0; i < TS; ++i)
                 sv[i] = srow[i][kg0 + g];
             uint32_t snz0[TS], snz1[TS];
-            if constexpr (KIND == KIND_TNN) {
+            if constexpr (KIND == KIND_TNN || KIND == KIND_TBN_SV) {
 #pragma unroll
                 for (int i = 0; i < TS; ++i) {
                     snz0[i] = sv[i].x | sv[i].z;
                     snz1[i] = sv[i].y | sv[i].w;
+                    if constexpr (KIND == KIND_TBN_SV)
+                        snnz[i] += __builtin_popcount(snz0[i]) + __builtin_popcount(snz1[i]);
                 }
             }
             VVec bnext = lds[buf][g * STRIDE + lane];
@@ -229,11 +241,17 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                         popc_acc(acc[0][i][t], m1);
                         popc_acc(acc[1][i][t], u1);
                     }
-                } else {
+                } else if constexpr (KIND == KIND_TBN) {
 #pragma unroll
                     for (int i = 0; i < TS; ++i) {
                         popc_acc(acc[0][i][t], xor_and_svv(sv[i].x, b.z, b.x));
                         popc_acc(acc[0][i][t], xor_and_svv(sv[i].y, b.w, b.y));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TS; ++i) {
+                        popc_acc(acc[0][i][t], xor_sv(sv[i].z, and_sv(snz0[i], b.x)));
+                        popc_acc(acc[0][i][t], xor_sv(sv[i].w, and_sv(snz1[i], b.y)));
                     }
                 }
             }
@@ -276,11 +294,22 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                             popc_acc(acc[0][i][t], m1);
                             popc_acc(acc[1][i][t], u1);
                         }
-                    } else {
+                    } else if constexpr (KIND == KIND_TBN) {
 #pragma unroll
                         for (int i = 0; i < TS; ++i) {
                             popc_acc(acc[0][i][t], xor_and_svv(sw[i].w[q * 2], bb.z, bb.x));
                             popc_acc(acc[0][i][t], xor_and_svv(sw[i].w[q * 2 + 1], bb.w, bb.y));
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < TS; ++i) {
+                            const uint32_t p0 = sw[i].w[q * 4], p1 = sw[i].w[q * 4 + 1];
+                            const uint32_t n0 = sw[i].w[q * 4 + 2], n1 = sw[i].w[q * 4 + 3];
+                            const uint32_t z0 = p0 | n0, z1 = p1 | n1;
+                            if (t == 0)  // uniform values: counted once per string on the scalar ALU
+                                snnz[i] += __builtin_popcount(z0) + __builtin_popcount(z1);
+                            popc_acc(acc[0][i][t], xor_sv(n0, and_sv(z0, bb.x)));
+                            popc_acc(acc[0][i][t], xor_sv(n1, and_sv(z1, bb.y)));
                         }
                     }
                 }
@@ -335,8 +364,10 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                 out[i] = K - 2 * acc[0][i][t];
             else if constexpr (KIND == KIND_TNN)
                 out[i] = acc[0][i][t] - 2 * acc[1][i][t];
-            else
+            else if constexpr (KIND == KIND_TBN)
                 out[i] = nnz[t] - 2 * acc[0][i][t];
+            else
+                out[i] = snnz[i] - 2 * acc[0][i][t];
         }
         if (tr) {
             if (q_out != nullptr) {
@@ -551,6 +582,16 @@ const GemmVariant kTbn[] = {
     LB_SMALL(1800, 18, KIND_TBN, 4, 1, 8, 16, 8),
 };
 
+// ternary operand on the scalar side: the scalar loads are those of the TNN instances
+const GemmVariant kTbnSv[] = {
+    LB_VARIANT(1, KIND_TBN_SV, 4, 1, 4, 16, 4),
+    LB_VARIANT(2, KIND_TBN_SV, 8, 1, 4, 8, 2),
+    LB_VARIANT(3, KIND_TBN_SV, 8, 2, 4, 4, 2),
+    LB_SMALL(300, 0, KIND_TBN_SV, 1, 1, 8, 16, 4),
+    LB_SMALL(600, 0, KIND_TBN_SV, 2, 1, 8, 16, 4),
+    LB_SMALL(1200, 0, KIND_TBN_SV, 4, 1, 8, 16, 4),
+};
+
 }  // namespace
 
 hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
@@ -584,6 +625,7 @@ const GemmVariant *gemm_variants(int kind, int *count)
     case KIND_BNN: *count = (int)(sizeof(kBnn) / sizeof(kBnn[0])); return kBnn;
     case KIND_TNN: *count = (int)(sizeof(kTnn) / sizeof(kTnn[0])); return kTnn;
     case KIND_TBN: *count = (int)(sizeof(kTbn) / sizeof(kTbn[0])); return kTbn;
+    case KIND_TBN_SV: *count = (int)(sizeof(kTbnSv) / sizeof(kTbnSv[0])); return kTbnSv;
     default: *count = 0; return nullptr;
     }
 }

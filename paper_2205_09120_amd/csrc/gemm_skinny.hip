@@ -10,7 +10,8 @@
 //   * each lane accumulates R x NS partial products over its depth slice in registers; at the end the wave
 //     reduces them across lanes with a halving butterfly (R*NS values shrink to one per lane pair) and
 //     writes int32 C.
-// Kinds: BNN (X, Y binary), TNN (X, Y ternary), TBN (X ternary, Y binary).
+// Kinds: BNN (X, Y binary), TNN (X, Y ternary), TBN (X ternary, Y binary), TBN_SV (X binary, Y ternary: gemm_tbn
+// with few ternary rows; the non-zero counts of the Y strings are taken while they are staged and summed in LDS).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -51,6 +52,7 @@ template <int KIND> struct SkTraits;
 template <> struct SkTraits<KIND_BNN> { using X = uint2; using Y = uint2; static constexpr int ACC = 1; };
 template <> struct SkTraits<KIND_TNN> { using X = uint4; using Y = uint4; static constexpr int ACC = 2; };
 template <> struct SkTraits<KIND_TBN> { using X = uint4; using Y = uint2; static constexpr int ACC = 1; };
+template <> struct SkTraits<KIND_TBN_SV> { using X = uint2; using Y = uint4; static constexpr int ACC = 1; };
 
 __device__ __forceinline__ uint2 zero2() { return make_uint2(0u, 0u); }
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
@@ -94,6 +96,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
     static_assert((V & (V - 1)) == 0 && V <= 64 && V >= 2, "R*NS must be a power of two <= 64");
 
     __shared__ YE ylds[NS][KC];
+    __shared__ int32_t ynnz[NS];  // TBN_SV: non-zero positions of each Y string
 
     const XE *__restrict__ Xp = static_cast<const XE *>(Xp_);
     const YE *__restrict__ Yp = static_cast<const YE *>(Yp_);
@@ -121,6 +124,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
 #pragma unroll
     for (int r = 0; r < R; ++r)
         nnz[r] = 0;
+    if constexpr (KIND == KIND_TBN_SV) {
+        if (tid < NS)
+            ynnz[tid] = 0;
+        __syncthreads();
+    }
 
     for (int kc = 0; kc < KW; kc += KC) {
         // Y loads are issued first (clamped addresses, no branches)
@@ -155,8 +163,15 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
 #pragma unroll
         for (int i = 0; i < YPT; ++i) {
             const int e = tid + i * NT;
-            if (NS * KC % NT == 0 || e < NS * KC)
-                ylds[e / KC][e % KC] = nz_neg(ypre[i]);
+            if (NS * KC % NT == 0 || e < NS * KC) {
+                const YE y = nz_neg(ypre[i]);
+                ylds[e / KC][e % KC] = y;
+                if constexpr (KIND == KIND_TBN_SV) {
+                    const int cnt = __builtin_popcount(y.x) + __builtin_popcount(y.y);
+                    if (cnt)
+                        atomicAdd(&ynnz[e / KC], cnt);
+                }
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -185,9 +200,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
                         popc_acc(acc[1][r][n], u0);
                         popc_acc(acc[0][r][n], m1);
                         popc_acc(acc[1][r][n], u1);
-                    } else {
+                    } else if constexpr (KIND == KIND_TBN) {
                         popc_acc(acc[0][r][n], xor_and_vvv(x[r].z, y.x, x[r].x));
                         popc_acc(acc[0][r][n], xor_and_vvv(x[r].w, y.y, x[r].y));
+                    } else {
+                        popc_acc(acc[0][r][n], xor_and_vvv(y.z, x[r].x, y.x));
+                        popc_acc(acc[0][r][n], xor_and_vvv(y.w, x[r].y, y.y));
                     }
                 }
             }
@@ -200,7 +218,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
     for (int r = 0; r < R; ++r)
 #pragma unroll
         for (int n = 0; n < NS; ++n) {
-            if constexpr (KIND == KIND_BNN)
+            if constexpr (KIND == KIND_BNN || KIND == KIND_TBN_SV)
                 val[r * NS + n] = acc[0][r][n];
             else if constexpr (KIND == KIND_TNN)
                 val[r * NS + n] = acc[0][r][n] - 2 * acc[1][r][n];
@@ -220,6 +238,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
             int32_t out = val[0];
             if constexpr (KIND == KIND_BNN)
                 out = K - 2 * out;
+            if constexpr (KIND == KIND_TBN_SV)
+                out = ynnz[n] - 2 * out;  // complete: the last staging was followed by a barrier
             const int64_t at = TR ? (int64_t)yn * ldc + xr : (int64_t)xr * ldc + yn;
             if (c16)
                 reinterpret_cast<int16_t *>(C)[at] = (int16_t)out;  // K <= 32767 checked on the host
@@ -250,7 +270,7 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
     int cfg = g_skinny_forced;
     if (cfg < 0) {
         if (a.rowsX >= 16384)
-            cfg = KIND == KIND_BNN ? 7 : KIND == KIND_TNN ? 3 : 1;
+            cfg = (KIND == KIND_BNN || KIND == KIND_TBN_SV) ? 7 : KIND == KIND_TNN ? 3 : 1;
         else if (a.rowsX >= 6144)
             cfg = 3;
         else if (a.rowsX >= 2048)
@@ -281,6 +301,7 @@ hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed)
     case KIND_BNN: return launch_kind<KIND_BNN>(a, transposed);
     case KIND_TNN: return launch_kind<KIND_TNN>(a, transposed);
     case KIND_TBN: return launch_kind<KIND_TBN>(a, transposed);
+    case KIND_TBN_SV: return launch_kind<KIND_TBN_SV>(a, transposed);
     default: return hipErrorInvalidValue;
     }
 }

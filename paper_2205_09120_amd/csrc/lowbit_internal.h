@@ -6,11 +6,14 @@
 
 namespace lowbit {
 
-enum Kind { KIND_BNN = 0, KIND_TNN = 1, KIND_TBN = 2 };
+// KIND_TBN_SV is the ternary-binary product with the TERNARY operand on the scalar side (launchers only: the C ABI
+// knows kinds 0..2 and gemm_tbn picks the orientation).
+enum Kind { KIND_BNN = 0, KIND_TNN = 1, KIND_TBN = 2, KIND_TBN_SV = 3 };
 
 // One tiled popcount GEMM launch.  S is the scalar-side packed operand (rowsS bit strings), V the vector-side
 // one (rowsV bit strings); product (s, v) is written to C[s*ldc + v], or to C[v*ldc + s] by the transposed
-// launcher.  Operand classes per kind: BNN S,V binary; TNN S,V ternary; TBN S binary, V ternary.
+// launcher.  Operand classes per kind: BNN S,V binary; TNN S,V ternary; TBN S binary, V ternary; TBN_SV S ternary,
+// V binary.
 struct GemmArgs {
     const uint32_t *Sp;
     const uint32_t *Vp;
@@ -68,7 +71,7 @@ hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t co
 
 // Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8
 // strings at a time).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.
-// Operand classes per kind: BNN X,Y binary; TNN X,Y ternary; TBN X ternary, Y binary.
+// Operand classes per kind: BNN X,Y binary; TNN X,Y ternary; TBN X ternary, Y binary; TBN_SV X binary, Y ternary.
 struct SkinnyArgs {
     const void *Xp;
     const void *Yp;
