@@ -232,6 +232,23 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
     a.ldc = ldc;
     a.c16 = c16 ? 1 : 0;
     a.stream = static_cast<hipStream_t>(stream);
+    // Few tiles and a long depth: every workgroup would walk the whole depth, one dependent memory round trip after
+    // the other, on a mostly idle machine.  Split the depth over enough workgroups to give each compute unit about
+    // six (at least 16 depth words per split); the partial products are added into a cleared C.  Only where lanes own
+    // columns of C, so that the atomic adds of a wave fall into one row (measured: 128 x 128 x 16384 3x faster,
+    // 64 x 64 x 65536 11x; with lanes owning rows the scattered atomics cost more than the split gains).
+    if (!forced && !c16 && !transposed && KW >= 128) {
+        const int64_t tiles8 = ((int64_t)(a.rowsS + 7) / 8) * ((a.rowsV + 63) / 64);
+        int64_t nsplit = 1536 / tiles8;
+        if (nsplit > KW / 16)
+            nsplit = KW / 16;
+        if (tiles8 <= 208 && nsplit >= 2) {
+            const hipError_t e = lowbit::launch_gemm_splitk(kind, a, transposed, (int)nsplit);
+            if (e != hipSuccess)
+                return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+            return LB_OK;
+        }
+    }
     const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
     const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
     if (e != hipSuccess)

@@ -98,13 +98,17 @@ template <int KIND, int TV, int KG> struct TileLds {
     static constexpr int NNZ = KIND == KIND_TBN ? NV : 1;          // per-string non-zero counts (TBN only)
 };
 
-// One workgroup tile: S block sb, V block vb of the problem described by the arguments.  TRM selects where product
+// One workgroup tile: S block sb, V block vb of the problem described by the arguments.  KW depth words are
+// multiplied; consecutive strings lie ldk words apart (ldk = KW unless the launch splits the depth, in which case
+// Sp / Vp already point at the first word of this workgroup's depth range and K counts the positions of that range).
+// accum: the results are added to C with integer atomics (depth-split launches into a cleared C) instead of stored.  TRM selects where product
 // (s, v) goes: 0 -> C[s*ldc + v], 1 -> C[v*ldc + s] (or the re-quantized output), 2 -> decided by tr_rt at run time
 // (workgroup-uniform), for launches that mix both orientations.
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG, int TRM>
 __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, const uint32_t *__restrict__ Vp,
-                                               int rowsS, int rowsV, int KW, int K, int32_t *__restrict__ C,
-                                               int64_t ldc, int sb, int vb, bool tr_rt, bool c16,
+                                               int rowsS, int rowsV, int KW, int ldk, int K,
+                                               int32_t *__restrict__ C, int64_t ldc, int sb, int vb, bool tr_rt,
+                                               bool c16, bool accum,
                                                const int32_t *__restrict__ q_lo, const int32_t *__restrict__ q_hi,
                                                uint64_t *__restrict__ q_out, int q_planes,
                                                typename TileLds<KIND, TV, KG>::VVec *lds_base, int32_t *nnz_lds)
@@ -136,7 +140,7 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
     for (int i = 0; i < TS; ++i) {
         int r = s0 + i;
         r = r < rowsS ? r : rowsS - 1;
-        srow[i] = Sv + (int64_t)r * KW;
+        srow[i] = Sv + (int64_t)r * ldk;
     }
 
     int32_t acc[T::ACC][TS][TV];
@@ -175,7 +179,7 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             const int kg = kg0 + g;
             VVec e = zero_of(VVec{});
             if (v < rowsV && kg < KW)
-                e = Vv[(int64_t)v * KW + kg];
+                e = Vv[(int64_t)v * ldk + kg];
             pre[j] = e;
         }
     };
@@ -394,6 +398,13 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             }
         }
         if (v < rowsV) {
+            if (accum) {
+#pragma unroll
+                for (int i = 0; i < TS; ++i)
+                    if (s0 + i < rowsS)
+                        atomicAdd(tr ? C + (int64_t)v * ldc + s0 + i : C + (int64_t)(s0 + i) * ldc + v, out[i]);
+                continue;
+            }
             if (c16) {
                 // 16-bit C (the accumulator width of Section III; the host has checked K <= 32767, so |c| fits)
                 int16_t *C16 = reinterpret_cast<int16_t *>(C);
@@ -481,8 +492,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
         vb = idx / nSB;
         sb = idx - vb * nSB;
     }
-    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, K, C, ldc, sb, vb, TR, c16 != 0,
-                                                            q_lo, q_hi, q_out, q_planes, lds, nnz_lds);
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, TR ? 1 : 0>(Sp, Vp, rowsS, rowsV, KW, KW, K, C, ldc, sb, vb, TR,
+                                                            c16 != 0, false, q_lo, q_hi, q_out, q_planes, lds, nnz_lds);
 }
 
 // Grouped launch: many independent small problems in one grid.  The table (built on the host by plan_group) maps
@@ -507,8 +518,62 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_group_kernel(const GroupHeade
     const GroupRecord r = recs[p];
     const int local = (int)(bid - r.tile0);
     const int vb = local / r.nSB, sb = local - vb * r.nSB;
-    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 2>(r.Sp, r.Vp, r.rowsS, r.rowsV, r.KW, r.K, r.C, r.ldc, sb, vb,
-                                                   r.transposed != 0, false, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 2>(r.Sp, r.Vp, r.rowsS, r.rowsV, r.KW, r.KW, r.K, r.C, r.ldc, sb, vb,
+                                                   r.transposed != 0, false, false, nullptr, nullptr, nullptr, 0, lds,
+                                                   nnz_lds);
+}
+
+// Depth-split launch for products of few tiles and a long depth: workgroup (tile, z) multiplies depth words
+// [z * words_per_split, ...) of its tile and adds the partial results to C, which a fill kernel cleared before.
+// Exact in any order: the partial results of eq. (6) / (7) over disjoint depth ranges are integers that add up to C
+// (eq. (6): K - 2 * popcount over a range counts that range's positions).
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
+__global__ __launch_bounds__(64 * WAVES) void gemm_popc_splitk_kernel(const uint32_t *__restrict__ Sp,
+                                                                      const uint32_t *__restrict__ Vp, int rowsS,
+                                                                      int rowsV, int KW, int K, int32_t *__restrict__ C,
+                                                                      int64_t ldc, int nSB, int transposed,
+                                                                      int words_per_split)
+{
+    using L = TileLds<KIND, TV, KG>;
+    using T = Traits<KIND>;
+    __shared__ typename L::VVec lds[2 * L::STAGE];
+    __shared__ int32_t nnz_lds[L::NNZ];
+    const int tile = blockIdx.x, z = blockIdx.y;
+    const int vb = tile / nSB, sb = tile - vb * nSB;
+    const int kw0 = z * words_per_split;
+    const int kw1 = kw0 + words_per_split < KW ? kw0 + words_per_split : KW;
+    if (kw0 >= kw1)
+        return;
+    const int k_end = kw1 * 64 < K ? kw1 * 64 : K;
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 2>(Sp + (int64_t)kw0 * T::SD, Vp + (int64_t)kw0 * T::VD, rowsS, rowsV,
+                                                   kw1 - kw0, KW, k_end - kw0 * 64, C, ldc, sb, vb, transposed != 0,
+                                                   false, true, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
+}
+
+__global__ __launch_bounds__(256) void clear_c_kernel(int32_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N)
+{
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n < N)
+        C[(int64_t)blockIdx.y * ldc + n] = 0;
+}
+
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
+hipError_t launch_splitk(const GemmArgs &a, bool transposed, int nsplit)
+{
+    const int nSB = (a.rowsS + WAVES * TS - 1) / (WAVES * TS);
+    const int nVB = (a.rowsV + 64 * TV - 1) / (64 * TV);
+    const int64_t tiles = (int64_t)nSB * nVB;
+    const int wps = (a.KW + nsplit - 1) / nsplit;
+    const int nz = (a.KW + wps - 1) / wps;
+    const int64_t M = transposed ? a.rowsV : a.rowsS, N = transposed ? a.rowsS : a.rowsV;
+    if (tiles > 0x7fffffffLL || nz > 65535 || M > 65535)
+        return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(clear_c_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, a.stream, a.C, a.ldc, M,
+                       N);
+    hipLaunchKernelGGL((gemm_popc_splitk_kernel<KIND, TS, TV, WAVES, KG, SG>), dim3((unsigned)tiles, (unsigned)nz),
+                       dim3(64 * WAVES), 0, a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB,
+                       transposed ? 1 : 0, wps);
+    return hipGetLastError();
 }
 
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG, bool TR>
@@ -617,6 +682,18 @@ hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t co
         return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_gemm_splitk(int kind, const GemmArgs &a, bool transposed, int nsplit)
+{
+    // 8 x 64 tiles (one string per wave, 8 waves), the instance the selection takes for problems this small
+    switch (kind) {
+    case KIND_BNN: return launch_splitk<KIND_BNN, 1, 1, 8, 16, 8>(a, transposed, nsplit);
+    case KIND_TNN: return launch_splitk<KIND_TNN, 1, 1, 8, 16, 4>(a, transposed, nsplit);
+    case KIND_TBN: return launch_splitk<KIND_TBN, 1, 1, 8, 16, 8>(a, transposed, nsplit);
+    case KIND_TBN_SV: return launch_splitk<KIND_TBN_SV, 1, 1, 8, 16, 4>(a, transposed, nsplit);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 const GemmVariant *gemm_variants(int kind, int *count)

@@ -43,6 +43,10 @@ struct GemmVariant {
 
 const GemmVariant *gemm_variants(int kind, int *count);
 
+// Depth-split launch of the 8 x 64 instance for products of few tiles and a long depth: clears C (int32 only), then
+// adds the partial products of `nsplit` depth ranges with integer atomics.  Two kernels on a.stream.
+hipError_t launch_gemm_splitk(int kind, const GemmArgs &a, bool transposed, int nsplit);
+
 // Grouped launch: one grid covers `count` independent problems, each cut into kGroupTileS x kGroupTileV tiles.
 // The table is header, `count` records, then one uint32 per workgroup naming the record that owns it; it is built on
 // the host (api.hip), copied to the device by the caller and read by the kernel.

@@ -177,6 +177,23 @@ def test_gemm_skinny_shapes(kind):
 
 
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_depth_split(kind):
+    """Few tiles and a long depth: the depth is split over workgroups whose partial products are added into a cleared
+    C (int32 atomics).  Depths that are not multiples of 64 (eq. (6) needs the true depth of every range), ragged
+    tiles, a padded ldc whose padding must stay untouched, and a C that holds garbage before the call."""
+    for (M, N, K) in [(64, 64, 8192 + 70), (100, 200, 12001), (130, 257, 30000), (24, 700, 9000), (1, 64, 8192),
+                      (17, 65, 65536 + 1), (256, 256, 8192)]:
+        ldc = N + 3
+        say(f"gemm_{kind} depth-split M={M} N={N} K={K} ldc={ldc}")
+        A, B = synth.make_custom(kind, M, N, K, seed=M + 3 * N + K)
+        C = torch.full((M, ldc), 12345, dtype=torch.int32, device="cuda")
+        run_gemm(kind, A, B, C=C, ldc=ldc)
+        got = C.cpu().numpy()
+        assert np.array_equal(got[:, :N], oracle.gemm(A, B)), (M, N, K)
+        assert np.all(got[:, N:] == 12345)
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
 def test_gemm_paper_shape_grid(kind):
     """All 64 height x width x depth shapes of the paper's timing experiment (Section IV-B)."""
     for idx, (H, W, D) in enumerate(synth.paper_shape_grid()):
