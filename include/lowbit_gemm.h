@@ -116,7 +116,10 @@ LB_API int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t 
  *
  *   Ap        device, packed A: M bit strings of depth K (binary for gemm_bnn, ternary otherwise).
  *   Bp        device, packed B: N bit strings (the columns of B) of depth K (ternary for gemm_tnn, binary otherwise).
- *   C         device, int32, row-major M x N with leading dimension ldc >= N; overwritten (no accumulation into C).
+ *   C         device, int32, row-major M x N with leading dimension ldc >= N; overwritten (no accumulation into C;
+ *             its previous contents do not matter).  A call enqueues one kernel, or two for products of few tiles
+ *             and a long depth (C is cleared, then partial products of depth ranges are added with integer atomics):
+ *             C holds the result once the work enqueued by the call has completed, not before.
  *   K         true depth (pad bits of the last word must be 0 as pack_* writes them); 1 <= K <= 2^31 - 1.
  * The kernels evaluate algebraically equivalent forms of the paper's bit formulas (see the kernel sources);
  * the integers written are identical.  Packed operands holding the invalid ternary code (1,1) give undefined C.
