@@ -253,6 +253,13 @@ LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, 
  * Process-wide; not meant to be changed while other threads are inside gemm_* calls.
  */
 LB_API int lb_set_variant(int op, int variant);
+
+/*
+ * Which kernel a gemm_bnn / gemm_tnn / gemm_tbn call (c16 = 0) or a gemm_c16 call (c16 = 1) of this shape would run:
+ * host logic only, usable without a GPU.  kind 0 = BNN, 1 = TNN, 2 = TBN.  Returns a short description (thread-local
+ * host string, valid until the next call on the thread), or NULL for arguments the gemm calls would reject.
+ */
+LB_API const char *lb_describe_plan(int kind, int64_t M, int64_t N, int64_t K, int c16);
 LB_API int lb_num_variants(int op);
 LB_API const char *lb_variant_name(int op, int variant);
 

@@ -22,7 +22,7 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
            "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "lb_set_variant", "lb_num_variants",
-           "lb_variant_name", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
+           "lb_variant_name", "lb_describe_plan", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
 
 class GemmProblem(ctypes.Structure):
@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.lb_num_variants.argtypes = [ci]
         L.lb_variant_name.restype = ctypes.c_char_p
         L.lb_variant_name.argtypes = [ci, ci]
+        L.lb_describe_plan.restype = ctypes.c_char_p
+        L.lb_describe_plan.argtypes = [ci, i64, i64, i64, ci]
         _lib = L
     return _lib
 
@@ -252,6 +254,12 @@ def gemm_u8_mfma(M, N, K, A, lda, B, ldb, zA: int, zB: int, C=None, ldc=None, st
         ldc = C.stride(0)
     _check(lib().gemm_u8_mfma(M, N, K, _ptr(A), lda, _ptr(B), ldb, zA, zB, _ptr(C), ldc, _stream(stream)))
     return C
+
+
+def lb_describe_plan(kind, M: int, N: int, K: int, c16: bool = False) -> Optional[str]:
+    """Which kernel a gemm call of this shape would run (host logic, no GPU needed)."""
+    t = lib().lb_describe_plan(_OPS.get(kind, kind), M, N, K, 1 if c16 else 0)
+    return None if t is None else t.decode()
 
 
 def lb_calib_sink_bytes() -> int:

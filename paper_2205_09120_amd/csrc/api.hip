@@ -165,16 +165,19 @@ bool prefer_skinny(int64_t rows, int64_t narrow, int64_t K)
 // M is not.
 bool b_on_scalar_side(int kind, int64_t M, int64_t N) { return kind == lowbit::KIND_TBN || (N < 64 && M > N); }
 
-// c16: C is an int16_t matrix (passed as void through the int32_t pointer of the launch arguments).
-int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
-            void *C, int64_t ldc, void *stream, bool c16 = false)
-{
-    bool empty;
-    const int rc = check_gemm(name, M, N, K, Ap, Bp, C, ldc, &empty, c16 ? 2 : 4);
-    if (rc != LB_OK || empty)
-        return rc;
-    const int64_t KW = (K + 63) / 64;
+// How one gemm_bnn / gemm_tnn / gemm_tbn / gemm_c16 call is carried out: host logic only, no HIP call.
+struct GemmPlan {
+    enum Path { SKINNY, SPLIT, TILED } path;
+    int kind;         // launcher kind (KIND_TBN_SV when gemm_tbn swaps the operand roles)
+    bool transposed;  // tiled / split: B on the scalar side, lanes own rows of C; skinny: B is the streamed operand
+    int variant;      // tiled: index into gemm_variants(kind)
+    int nsplit;       // split: depth ranges
+};
 
+GemmPlan plan_gemm(int kind, int64_t M, int64_t N, int64_t K, bool c16)
+{
+    GemmPlan p{GemmPlan::TILED, kind, false, 0, 1};
+    const int64_t KW = (K + 63) / 64;
     int count = 0;
     const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
     const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
@@ -187,75 +190,92 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
         const bool skinny_n = narrow_n && prefer_skinny(M, N, K);
         const bool skinny_m = narrow_m && prefer_skinny(N, M, K);
         if (skinny_n || skinny_m) {
-            lowbit::SkinnyArgs sa;
-            sa.Xp = skinny_n ? Ap : Bp;
-            sa.Yp = skinny_n ? Bp : Ap;
-            sa.rowsX = (int)(skinny_n ? M : N);
-            sa.rowsY = (int)(skinny_n ? N : M);
-            sa.KW = (int)KW;
-            sa.K = (int)K;
-            sa.C = static_cast<int32_t *>(C);
-            sa.ldc = ldc;
-            sa.c16 = c16 ? 1 : 0;
-            sa.stream = static_cast<hipStream_t>(stream);
+            p.path = GemmPlan::SKINNY;
+            p.transposed = skinny_m;
             // gemm_tbn with few ternary rows: the binary operand is the streamed one
-            const int sk_kind = (kind == lowbit::KIND_TBN && skinny_m) ? lowbit::KIND_TBN_SV : kind;
-            const hipError_t e = lowbit::launch_gemm_skinny(sk_kind, sa, skinny_m);
-            if (e != hipSuccess)
-                return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
-            return LB_OK;
+            if (kind == lowbit::KIND_TBN && skinny_m)
+                p.kind = lowbit::KIND_TBN_SV;
+            return p;
         }
     }
-    lowbit::GemmArgs a;
     // gemm_tbn normally keeps the binary operand on the scalar side (2 instructions per word, lanes own rows of C).
     // With at most 32 ternary rows most of those lanes would idle: then the ternary operand goes to the scalar side
     // (3 instructions per word, lanes own columns of C).
     if (kind == lowbit::KIND_TBN && !forced && M <= 32 && N > M) {
-        kind = lowbit::KIND_TBN_SV;
-        tab = lowbit::gemm_variants(kind, &count);
+        p.kind = lowbit::KIND_TBN_SV;
+        tab = lowbit::gemm_variants(p.kind, &count);
     }
-    const bool transposed = kind != lowbit::KIND_TBN_SV && b_on_scalar_side(kind, M, N);
-    if (transposed) {
-        a.Sp = reinterpret_cast<const uint32_t *>(Bp);
-        a.rowsS = (int)N;
-        a.Vp = reinterpret_cast<const uint32_t *>(Ap);
-        a.rowsV = (int)M;
-    } else {
-        a.Sp = reinterpret_cast<const uint32_t *>(Ap);
-        a.rowsS = (int)M;
-        a.Vp = reinterpret_cast<const uint32_t *>(Bp);
-        a.rowsV = (int)N;
-    }
-    a.KW = (int)KW;
-    a.K = (int)K;
-    a.C = static_cast<int32_t *>(C);
-    a.ldc = ldc;
-    a.c16 = c16 ? 1 : 0;
-    a.stream = static_cast<hipStream_t>(stream);
+    p.transposed = p.kind != lowbit::KIND_TBN_SV && b_on_scalar_side(p.kind, M, N);
+    const int64_t rowsS = p.transposed ? N : M, rowsV = p.transposed ? M : N;
     // Few tiles and a long depth: every workgroup would walk the whole depth, one dependent memory round trip after
     // the other, on a mostly idle machine.  Split the depth over enough workgroups to give each compute unit about
     // six (at least 16 depth words per split); the partial products are added into a cleared C.  Only where lanes own
     // columns of C, so that the atomic adds of a wave fall into one row (measured: 128 x 128 x 16384 3x faster,
     // 64 x 64 x 65536 11x; with lanes owning rows the scattered atomics cost more than the split gains).
-    if (!forced && !c16 && !transposed && KW >= 128) {
-        const int64_t tiles8 = ((int64_t)(a.rowsS + 7) / 8) * ((a.rowsV + 63) / 64);
+    if (!forced && !c16 && !p.transposed && KW >= 128 && M <= 65535) {
+        const int64_t tiles8 = ((rowsS + 7) / 8) * ((rowsV + 63) / 64);
         int64_t nsplit = 1536 / tiles8;
         if (nsplit > KW / 16)
             nsplit = KW / 16;
         if (tiles8 <= 208 && nsplit >= 2) {
-            const hipError_t e = lowbit::launch_gemm_splitk(kind, a, transposed, (int)nsplit);
-            if (e != hipSuccess)
-                return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
-            return LB_OK;
+            p.path = GemmPlan::SPLIT;
+            p.nsplit = (int)nsplit;
+            return p;
         }
     }
-    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
-    const hipError_t e = transposed ? tab[v].launch_transposed(a) : tab[v].launch(a);
+    p.variant = forced ? g_forced[kind] : choose_variant(tab, count, rowsS, rowsV, KW);
+    return p;
+}
+
+// c16: C is an int16_t matrix (passed as void through the int32_t pointer of the launch arguments).
+int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const uint64_t *Ap, const uint64_t *Bp,
+            void *C, int64_t ldc, void *stream, bool c16 = false)
+{
+    bool empty;
+    const int rc = check_gemm(name, M, N, K, Ap, Bp, C, ldc, &empty, c16 ? 2 : 4);
+    if (rc != LB_OK || empty)
+        return rc;
+    const int64_t KW = (K + 63) / 64;
+    const GemmPlan p = plan_gemm(kind, M, N, K, c16);
+    hipError_t e;
+    if (p.path == GemmPlan::SKINNY) {
+        const bool b_streamed = p.transposed;
+        lowbit::SkinnyArgs sa;
+        sa.Xp = b_streamed ? Bp : Ap;
+        sa.Yp = b_streamed ? Ap : Bp;
+        sa.rowsX = (int)(b_streamed ? N : M);
+        sa.rowsY = (int)(b_streamed ? M : N);
+        sa.KW = (int)KW;
+        sa.K = (int)K;
+        sa.C = static_cast<int32_t *>(C);
+        sa.ldc = ldc;
+        sa.c16 = c16 ? 1 : 0;
+        sa.stream = static_cast<hipStream_t>(stream);
+        e = lowbit::launch_gemm_skinny(p.kind, sa, b_streamed);
+    } else {
+        lowbit::GemmArgs a;
+        a.Sp = reinterpret_cast<const uint32_t *>(p.transposed ? Bp : Ap);
+        a.rowsS = (int)(p.transposed ? N : M);
+        a.Vp = reinterpret_cast<const uint32_t *>(p.transposed ? Ap : Bp);
+        a.rowsV = (int)(p.transposed ? M : N);
+        a.KW = (int)KW;
+        a.K = (int)K;
+        a.C = static_cast<int32_t *>(C);
+        a.ldc = ldc;
+        a.c16 = c16 ? 1 : 0;
+        a.stream = static_cast<hipStream_t>(stream);
+        if (p.path == GemmPlan::SPLIT) {
+            e = lowbit::launch_gemm_splitk(p.kind, a, p.transposed, p.nsplit);
+        } else {
+            int count = 0;
+            const lowbit::GemmVariant *tab = lowbit::gemm_variants(p.kind, &count);
+            e = p.transposed ? tab[p.variant].launch_transposed(a) : tab[p.variant].launch(a);
+        }
+    }
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;
 }
-
 
 // Validates every problem of a group and counts the workgroups the launch needs.
 int group_workgroups(int kind, const char *name, int64_t count, const lb_gemm_problem *problems, int64_t *workgroups)
@@ -626,6 +646,27 @@ int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, void *s
     if (e != hipSuccess)
         return fail(LB_EHIP, "lb_calib_stream: %s", hipGetErrorString(e));
     return LB_OK;
+}
+
+const char *lb_describe_plan(int kind, int64_t M, int64_t N, int64_t K, int c16)
+{
+    thread_local char text[160];
+    if (kind < 0 || kind > 2 || M <= 0 || N <= 0 || K <= 0 || K > kMaxDepth || M > kMaxExtent || N > kMaxExtent)
+        return nullptr;
+    const GemmPlan p = plan_gemm(kind, M, N, K, c16 != 0);
+    static const char *const kinds[] = {"bnn", "tnn", "tbn", "tbn (ternary operand on the scalar side / in LDS)"};
+    if (p.path == GemmPlan::SKINNY) {
+        snprintf(text, sizeof(text), "%s depth-split-across-lanes kernel, %s streamed", kinds[p.kind],
+                 p.transposed ? "B" : "A");
+    } else if (p.path == GemmPlan::SPLIT) {
+        snprintf(text, sizeof(text), "%s tiled kernel, %d depth ranges added into a cleared C", kinds[p.kind], p.nsplit);
+    } else {
+        int count = 0;
+        const lowbit::GemmVariant *tab = lowbit::gemm_variants(p.kind, &count);
+        snprintf(text, sizeof(text), "%s tiled kernel [%s], %s on the scalar side", kinds[p.kind], tab[p.variant].name,
+                 p.transposed ? "B" : "A");
+    }
+    return text;
 }
 
 int lb_set_variant(int op, int variant)

@@ -230,3 +230,35 @@ def test_grouped_argument_validation(L):
     # an empty group plans to a header-only table
     table, wg2 = binding.gemm_grouped_plan("bnn", [])
     assert wg2 == 0 and table.numel() == 16
+
+
+def test_dispatch_plan_is_host_logic(L):
+    """Which kernel a call would run, decided on the host: the headline shape takes the large tile, the
+    fully connected configuration the depth-split-across-lanes kernel, many shallow rows the tiled kernel with a low
+    tile, few tiles with a long depth the depth ranges, gemm_tbn with few ternary rows the swapped roles."""
+    d = binding.lb_describe_plan
+    assert d("tnn", 1024, 50176, 4608) == "tnn tiled kernel [KIND_TNN ts8 tv4 w4 kg4 sg2], A on the scalar side"
+    assert d("tnn", 64, 256, 576) == "tnn tiled kernel [KIND_TNN ts1 tv1 w8 kg16 sg4], A on the scalar side"
+    assert d("bnn", 256, 3136, 1152) == "bnn tiled kernel [KIND_BNN ts4 tv1 w8 kg16 sg8], A on the scalar side"
+    assert d("tbn", 512, 784, 2304) == "tbn tiled kernel [KIND_TBN ts4 tv1 w8 kg16 sg8], B on the scalar side"
+    for kind in ("tnn", "tbn", "bnn"):
+        assert d(kind, 4096, 8, 16384) == f"{kind} depth-split-across-lanes kernel, A streamed"
+        # many shallow rows: not the depth-split kernel, but 8-row tiles with the 8 strings of B in scalar registers
+        t = d(kind, 100000, 8, 576)
+        assert "tiled kernel" in t and " ts1 tv1 w8 " in t and t.endswith("B on the scalar side")
+        # 9..16 short strings: 16-row tiles once the problem is large
+        assert " ts4 tv1 w4 " in d(kind, 262144, 16, 1024)
+    assert d("tnn", 128, 128, 16384).startswith("tnn tiled kernel, ") and "depth ranges" in d("tnn", 128, 128, 16384)
+    assert "depth ranges" not in d("tnn", 128, 128, 16384, c16=True)        # a 16-bit C cannot take atomic adds
+    assert "depth ranges" not in d("tnn", 4096, 32, 16384)                  # lanes own rows of C: no split
+    assert "depth ranges" not in d("tnn", 128, 128, 4608)                   # too shallow to pay for a cleared C
+    assert d("tbn", 8, 50176, 4608).startswith("tbn (ternary operand on the scalar side")
+    assert d("tbn", 8, 4096, 16384) == "tbn (ternary operand on the scalar side / in LDS) " \
+                                         "depth-split-across-lanes kernel, B streamed"
+    assert d("tbn", 48, 50176, 4608).startswith("tbn tiled kernel")         # enough ternary rows: binary on scalar side
+    assert d("tnn", 0, 5, 64) is None and d("tnn", 4, 4, 0) is None and L.lb_describe_plan(7, 4, 4, 64, 0) is None
+    try:
+        assert L.lb_set_variant(1, 0) == binding.LB_OK                      # a forced variant overrides all of it
+        assert d("tnn", 4096, 8, 16384) == "tnn tiled kernel [KIND_TNN ts4 tv1 w4 kg16 sg4], B on the scalar side"
+    finally:
+        L.lb_set_variant(1, -1)
