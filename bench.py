@@ -398,6 +398,17 @@ def main() -> int:
                 others[name]["hbm_frac_cold_operand"] = packed_bytes / cold / 1e9 / HBM_PEAK_GBS
                 others[name]["read_only_kernel_same_cold_bytes_us"] = floor * 1e6
         extra["other_configs_gemm_only_warm"] = others
+        # shapes outside the configurations that exercise the other dispatch paths (graph replay, operands warm)
+        paths = {}
+        for kind, (m_, n_, k_) in (("tnn", (100000, 16, 576)), ("tbn", (8, 50176, 4608)), ("tnn", (128, 128, 16384)),
+                                   ("bnn", (64, 64, 65536)), ("tbn", (8, 4096, 16384))):
+            a_, b_ = synth.make_custom(kind, m_, n_, k_, seed=77)
+            ap_, bp_ = lb.pack_a(kind, torch.from_numpy(a_).cuda()), lb.pack_b(kind, torch.from_numpy(b_).cuda())
+            c_ = torch.empty((m_, n_), dtype=torch.int32, device="cuda")
+            t = graph_time(lambda: lb.gemm(kind, m_, n_, k_, ap_, bp_, c_, n_), 10, 10)
+            paths[f"{kind}_{m_}x{n_}x{k_}"] = {"gemm_us": t * 1e6, "tops": 2.0 * m_ * n_ * k_ / t / 1e12,
+                                              "plan": lb.lb_describe_plan(kind, m_, n_, k_)}
+        extra["dispatch_paths"] = paths
     out["extra"] = extra
 
     if not args.no_cpu_baseline:
