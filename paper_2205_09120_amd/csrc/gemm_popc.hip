@@ -550,7 +550,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_splitk_kernel(const uint
                                                    false, true, nullptr, nullptr, nullptr, 0, lds, nnz_lds);
 }
 
-__global__ __launch_bounds__(256) void clear_c_kernel(int32_t *__restrict__ C, int64_t ldc, int64_t M, int64_t N)
+// zeroes the M x N part of C (row = blockIdx.y); the padding between N and ldc is left alone
+__global__ __launch_bounds__(256) void clear_c_kernel(int32_t *__restrict__ C, int64_t ldc, int64_t N)
 {
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n < N)
@@ -568,8 +569,7 @@ hipError_t launch_splitk(const GemmArgs &a, bool transposed, int nsplit)
     const int64_t M = transposed ? a.rowsV : a.rowsS, N = transposed ? a.rowsS : a.rowsV;
     if (tiles > 0x7fffffffLL || nz > 65535 || M > 65535)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(clear_c_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, a.stream, a.C, a.ldc, M,
-                       N);
+    hipLaunchKernelGGL(clear_c_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, a.stream, a.C, a.ldc, N);
     hipLaunchKernelGGL((gemm_popc_splitk_kernel<KIND, TS, TV, WAVES, KG, SG>), dim3((unsigned)tiles, (unsigned)nz),
                        dim3(64 * WAVES), 0, a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB,
                        transposed ? 1 : 0, wps);
