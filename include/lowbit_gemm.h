@@ -242,7 +242,8 @@ LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, 
 /*
  * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
  *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
- *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel,
+ *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel (forcing one
+ *            also sends every product with at most 32 strings on one side to that kernel),
  *            4 = kernel instance of gemm_i8_mfma (0..2: 4-wave tiles 128x128, 256x256, 256x128; 3..5: wave-specialised
  *            256x128 with 3, 2, 4 depth steps of prefetch; 6: direct-to-LDS 256x128 with 64-byte depth stages;
  *            7, 8, 9: direct-to-LDS 256x128 / 128x128 / 64x64 tiles with 128-byte stages where the depth allows;

@@ -27,7 +27,7 @@ int fail(int code, const char *fmt, ...)
 constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K must fit
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
-constexpr int64_t kSkinnyMax = 16;             // widest "skinny" side served by the depth-split kernel
+constexpr int64_t kSkinnyMax = 32;             // widest "skinny" side served by the depth-split kernel
 constexpr int kI8Instances = 10;               // kernel instances of gemm_i8_mfma selectable through lb_set_variant
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -147,17 +147,23 @@ int check_gemm(const char *name, int64_t M, int64_t N, int64_t K, const uint64_t
     return LB_OK;
 }
 
-// Depth-split (skinny) kernel or tiled kernel for a product with at most 16 strings on one side?  The skinny kernel
-// streams the `rows` long strings once per 8 short ones and pays a cross-lane reduction per row, so it wins when the
-// depth is large against the row count; the tiled kernel wins on many shallow rows (measured over rows 1 K .. 256 K,
-// depth 1 K .. 64 K, 1 / 8 / 16 short strings: up to 10x either way).
+// Depth-split (skinny) kernel or tiled kernel for a product with at most 32 strings on one side?  The skinny kernel
+// streams the `rows` long strings once (8, 16 or 32 short strings per workgroup) and pays a cross-lane reduction per
+// row, so it wins when the depth is large against the row count; the tiled kernel wins on many shallow rows (measured
+// over rows 1 K .. 256 K, depth 1 K .. 64 K, 1 .. 32 short strings: up to 10x either way).
 bool prefer_skinny(int64_t rows, int64_t narrow, int64_t K)
 {
+    if (lowbit::skinny_forced_config() >= 0)  // a forced configuration of that kernel also forces the kernel
+        return true;
     if (K < 2048)
         return false;
     if (narrow <= 8)
         return K >= 16384 || rows <= K;
-    return rows <= (K < 16384 ? K : 16384);
+    if (K < 4096)
+        return false;
+    if (narrow <= 16)
+        return rows <= (K < 16384 ? K : 16384);
+    return rows <= (K / 4 < 8192 ? K / 4 : 8192);
 }
 
 // Which operand rides in scalar registers.  TBN: always the binary one (one scalar source per instruction), so lanes

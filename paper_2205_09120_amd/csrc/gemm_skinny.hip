@@ -3,7 +3,8 @@
 // The products are those of eq. (6) / (7) of the paper, evaluated in the same reduced forms as the tiled kernels
 // (see gemm_popc.hip).  What differs is the decomposition, because the work is bound by streaming the large
 // operand ("X", rowsX bit strings) from HBM exactly once:
-//   * the small operand ("Y", at most NS = 8 bit strings per workgroup column block) is staged in LDS,
+//   * the small operand ("Y", NS = 8, 16 or 32 bit strings per workgroup column block: the smallest that holds all
+//     of them, so that X is streamed once) is staged in LDS,
 //     converted to (nz, neg) planes when ternary;
 //   * a wave owns R strings of X and its 64 lanes split the depth: lane l takes depth words l, l+64, ... of the
 //     current chunk, so every load instruction of a wave reads one contiguous kilobyte of X;
@@ -20,9 +21,9 @@
 namespace lowbit {
 namespace {
 
-constexpr int NS = 8;     // strings of Y per workgroup
-constexpr int KC = 256;   // depth words per LDS chunk (4 per lane)
-constexpr int JW = KC / 64;
+// NS strings of Y per workgroup; KC depth words per LDS chunk (JW per lane), smaller for more strings so that the
+// chunk stays within 64 KB of LDS
+template <int NS> struct SkChunk { static constexpr int KC = NS <= 8 ? 256 : NS == 16 ? 256 : 128; };
 
 __device__ __forceinline__ uint32_t and_vv(uint32_t a, uint32_t b)
 {
@@ -84,7 +85,7 @@ template <int CNT, int BIT> __device__ __forceinline__ void reduce_halving(int32
     }
 }
 
-template <int KIND, int R, int WAVES, bool TR>
+template <int KIND, int R, int WAVES, bool TR, int NS = 8>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__restrict__ Xp_, const void *__restrict__ Yp_,
                                                           int rowsX, int rowsY, int KW, int K,
                                                           int32_t *__restrict__ C, int64_t ldc, int c16)
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
     using T = SkTraits<KIND>;
     using XE = typename T::X;
     using YE = typename T::Y;
+    constexpr int KC = SkChunk<NS>::KC, JW = KC / 64;
     constexpr int V = R * NS;  // partial sums per lane
     static_assert((V & (V - 1)) == 0 && V <= 64 && V >= 2, "R*NS must be a power of two <= 64");
 
@@ -249,13 +251,13 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
     }
 }
 
-template <int KIND, int R, int WAVES, bool TR> hipError_t launch_sk(const SkinnyArgs &a)
+template <int KIND, int R, int WAVES, bool TR, int NS = 8> hipError_t launch_sk(const SkinnyArgs &a)
 {
     const int64_t gx = ((int64_t)a.rowsX + WAVES * R - 1) / (WAVES * R);
     const int64_t gy = ((int64_t)a.rowsY + NS - 1) / NS;
     if (gx > 0x7fffffffLL || gy > 65535)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_skinny_kernel<KIND, R, WAVES, TR>), dim3((unsigned)gx, (unsigned)gy), dim3(64 * WAVES),
+    hipLaunchKernelGGL((gemm_skinny_kernel<KIND, R, WAVES, TR, NS>), dim3((unsigned)gx, (unsigned)gy), dim3(64 * WAVES),
                        0, a.stream, a.Xp, a.Yp, a.rowsX, a.rowsY, a.KW, a.K, a.C, a.ldc, a.c16);
     return hipGetLastError();
 }
@@ -277,6 +279,25 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
             cfg = 5;
         else
             cfg = 2;
+        if (a.rowsY > 16 && a.rowsX >= 2048)
+            cfg = 3;  // 32 strings per workgroup: 2 rows per wave halve the LDS reads per product
+    }
+    // more than 8 short strings: 16 or 32 per workgroup (the long operand is still streamed once), with the
+    // configurations whose R x NS partial sums fit a lane
+    if (a.rowsY > 8) {
+        const bool wide = a.rowsY > 16;
+#define LB_SK_NS(R, W)                                                                                          \
+    (wide ? (tr ? launch_sk<KIND, R, W, true, 32>(a) : launch_sk<KIND, R, W, false, 32>(a))                    \
+          : (tr ? launch_sk<KIND, R, W, true, 16>(a) : launch_sk<KIND, R, W, false, 16>(a)))
+        switch (cfg) {
+        case 1: return LB_SK_NS(2, 4);
+        case 0:
+        case 3:
+        case 6:
+        case 7: return LB_SK_NS(2, 8);
+        default: return LB_SK_NS(1, 8);  // 16 waves of 1 row would spill: 32 x 2 accumulators at 128 registers
+        }
+#undef LB_SK_NS
     }
     switch (cfg) {
     case 0: return tr ? launch_sk<KIND, 4, 4, true>(a) : launch_sk<KIND, 4, 4, false>(a);
@@ -294,6 +315,7 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
 
 int skinny_num_configs() { return 8; }
 void skinny_force_config(int cfg) { g_skinny_forced = cfg; }
+int skinny_forced_config() { return g_skinny_forced; }
 
 hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed)
 {

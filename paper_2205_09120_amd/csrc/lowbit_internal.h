@@ -73,8 +73,8 @@ static_assert(sizeof(GroupHeader) == 16 && sizeof(GroupRecord) == 64, "table lay
 hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
                              hipStream_t stream);
 
-// Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8
-// strings at a time).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.
+// Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8, 16 or
+// 32 strings at a time: X is streamed once for up to 32).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.
 // Operand classes per kind: BNN X,Y binary; TNN X,Y ternary; TBN X ternary, Y binary; TBN_SV X binary, Y ternary.
 struct SkinnyArgs {
     const void *Xp;
@@ -88,6 +88,7 @@ struct SkinnyArgs {
 hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed);
 int skinny_num_configs();
 void skinny_force_config(int cfg);  // -1 = shape-based
+int skinny_forced_config();
 
 // Packing launchers (pack.hip).  Element (r,k) = src[r*stride_r + k*stride_k].
 hipError_t launch_pack(bool ternary, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,

@@ -250,12 +250,15 @@ def test_dispatch_plan_is_host_logic(L):
         assert " ts4 tv1 w4 " in d(kind, 262144, 16, 1024)
     assert d("tnn", 128, 128, 16384).startswith("tnn tiled kernel, ") and "depth ranges" in d("tnn", 128, 128, 16384)
     assert "depth ranges" not in d("tnn", 128, 128, 16384, c16=True)        # a 16-bit C cannot take atomic adds
-    assert "depth ranges" not in d("tnn", 4096, 32, 16384)                  # lanes own rows of C: no split
+    assert "depth ranges" not in d("tnn", 4096, 48, 16384)                  # lanes own rows of C: no split
     assert "depth ranges" not in d("tnn", 128, 128, 4608)                   # too shallow to pay for a cleared C
     assert d("tbn", 8, 50176, 4608).startswith("tbn (ternary operand on the scalar side")
     assert d("tbn", 8, 4096, 16384) == "tbn (ternary operand on the scalar side / in LDS) " \
                                          "depth-split-across-lanes kernel, B streamed"
     assert d("tbn", 48, 50176, 4608).startswith("tbn tiled kernel")         # enough ternary rows: binary on scalar side
+    assert "depth-split-across-lanes" in d("tnn", 4096, 32, 16384)          # up to 32 short strings, deep and few rows
+    assert "tiled kernel" in d("tnn", 65536, 32, 16384) and "tiled kernel" in d("tnn", 4096, 32, 2304)
+    assert "tiled kernel" in d("tnn", 4096, 33, 16384)
     assert d("tnn", 0, 5, 64) is None and d("tnn", 4, 4, 0) is None and L.lb_describe_plan(7, 4, 4, 64, 0) is None
     try:
         assert L.lb_set_variant(1, 0) == binding.LB_OK                      # a forced variant overrides all of it

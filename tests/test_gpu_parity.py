@@ -161,6 +161,9 @@ SKINNY_SHAPES = [(64, 1, 64), (64, 8, 1), (100, 9, 16384 + 70), (4096, 16, 300),
                  # deep enough for the depth-split kernel (depth >= 2048 and not many more rows than depth) ...
                  (300, 8, 2048 + 70), (4096, 16, 4100), (2100, 5, 2049), (5, 3000, 4000), (9, 2500, 2304),
                  (20000, 2, 16384 + 64), (7000, 11, 9000),
+                 # 9..32 short strings: 16 or 32 of them per workgroup, the long operand still streamed once
+                 (1000, 12, 5000), (2000, 16, 4096), (1000, 24, 8192 + 70), (2048, 32, 16384), (900, 17, 4100),
+                 (20, 3000, 16384), (32, 1030, 9000),
                  # ... and narrow shapes that the tiled kernel serves: many shallow rows, 1 / 8 / 16 strings
                  (30000, 1, 600), (30000, 8, 1000), (30000, 13, 2500), (20000, 16, 20000 // 8), (12, 30000, 1000)]
 
@@ -174,6 +177,28 @@ def test_gemm_skinny_shapes(kind):
         A, B = synth.make_custom(kind, M, N, K, seed=M + 5 * N + 11 * K)
         got = run_gemm(kind, A, B).cpu().numpy()
         assert np.array_equal(got, oracle.gemm(A, B)), (M, N, K)
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_skinny_every_configuration(kind):
+    """Every (rows per wave, waves per workgroup) configuration of the depth-split kernel, for 8, 16 and 32 short
+    strings per workgroup and both operand roles; forcing a configuration also forces that kernel."""
+    shapes = [(300, 5, 700), (130, 13, 1000), (70, 29, 600), (7, 200, 900), (31, 150, 1300), (257, 32, 2048 + 64)]
+    try:
+        for cfg in range(lb.lb_num_variants(3)):
+            lb.lb_set_variant(3, cfg)
+            for (M, N, K) in shapes:
+                say(f"gemm_{kind} skinny configuration {cfg} M={M} N={N} K={K}")
+                assert "depth-split-across-lanes" in lb.lb_describe_plan(kind, M, N, K)
+                A, B = synth.make_custom(kind, M, N, K, seed=cfg * 100 + M + N)
+                ldc = N + 2
+                C = torch.full((M, ldc), -5, dtype=torch.int32, device="cuda")
+                run_gemm(kind, A, B, C=C, ldc=ldc)
+                got = C.cpu().numpy()
+                assert np.array_equal(got[:, :N], oracle.gemm(A, B)), (cfg, M, N, K)
+                assert np.all(got[:, N:] == -5)
+    finally:
+        lb.lb_set_variant(3, -1)
 
 
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
