@@ -215,10 +215,11 @@ GemmPlan plan_gemm(int kind, int64_t M, int64_t N, int64_t K, bool c16)
     const int64_t rowsS = p.transposed ? N : M, rowsV = p.transposed ? M : N;
     // Few tiles and a long depth: every workgroup would walk the whole depth, one dependent memory round trip after
     // the other, on a mostly idle machine.  Split the depth over enough workgroups to give each compute unit about
-    // six (at least 16 depth words per split); the partial products are added into a cleared C.  Only where lanes own
-    // columns of C, so that the atomic adds of a wave fall into one row (measured: 128 x 128 x 16384 3x faster,
-    // 64 x 64 x 65536 11x; with lanes owning rows the scattered atomics cost more than the split gains).
-    if (!forced && !c16 && !p.transposed && KW >= 128 && M <= 65535) {
+    // six (at least 16 depth words per split); the partial products are added into a cleared C (measured: 128 x 128 x
+    // 16384 3x faster, 64 x 64 x 65536 11x, 512 x 49 x 65536 3x; below these depths the cleared C and the atomic adds
+    // cost more than the split gains).
+    const int64_t split_min_kw = kind == lowbit::KIND_TNN ? 128 : 160;
+    if (!forced && !c16 && KW >= split_min_kw && M <= 65535) {
         const int64_t tiles8 = ((rowsS + 7) / 8) * ((rowsV + 63) / 64);
         int64_t nsplit = 1536 / tiles8;
         if (nsplit > KW / 16)

@@ -397,12 +397,32 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                 continue;
             }
         }
+        if (accum && tr) {
+            // lanes own rows of C here: adding straight from the registers would touch 64 rows per instruction.  The
+            // workgroup's (WAVES*TS) x 64 results go through LDS (the tile buffers are free after the main loop), so
+            // that consecutive threads add to consecutive columns of a row.
+            constexpr int SW = WAVES * TS;
+            int32_t *stage = reinterpret_cast<int32_t *>(lds_base);
+            static_assert(SW * 64 * 4 <= (int)sizeof(VVec) * 2 * KG * STRIDE, "staging must fit the tile buffers");
+            __syncthreads();  // every wave is done with the tile buffers (and with the staging of the previous t)
+#pragma unroll
+            for (int i = 0; i < TS; ++i)
+                stage[lane * SW + wave * TS + i] = out[i];
+            __syncthreads();
+            for (int e = threadIdx.x; e < SW * 64; e += 64 * WAVES) {
+                const int vl = e / SW, sl = e - vl * SW;
+                const int vv = v0 + t * 64 + vl, ss = sb * SW + sl;
+                if (vv < rowsV && ss < rowsS)
+                    atomicAdd(C + (int64_t)vv * ldc + ss, stage[e]);
+            }
+            continue;
+        }
         if (v < rowsV) {
             if (accum) {
 #pragma unroll
                 for (int i = 0; i < TS; ++i)
                     if (s0 + i < rowsS)
-                        atomicAdd(tr ? C + (int64_t)v * ldc + s0 + i : C + (int64_t)(s0 + i) * ldc + v, out[i]);
+                        atomicAdd(C + (int64_t)(s0 + i) * ldc + v, out[i]);
                 continue;
             }
             if (c16) {
@@ -619,6 +639,7 @@ const GemmVariant kBnn[] = {
     LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
     LB_SMALL(64, 0, KIND_BNN, 1, 1, 4, 16, 8),
     LB_SMALL(160, 0, KIND_BNN, 1, 1, 8, 16, 8),
+    LB_SMALL(300, 18, KIND_BNN, 1, 1, 8, 16, 8),
     LB_SMALL(600, 0, KIND_BNN, 2, 1, 8, 16, 8),
     LB_SMALL(1200, 0, KIND_BNN, 4, 1, 8, 16, 8),
 };

@@ -250,7 +250,8 @@ def test_dispatch_plan_is_host_logic(L):
         assert " ts4 tv1 w4 " in d(kind, 262144, 16, 1024)
     assert d("tnn", 128, 128, 16384).startswith("tnn tiled kernel, ") and "depth ranges" in d("tnn", 128, 128, 16384)
     assert "depth ranges" not in d("tnn", 128, 128, 16384, c16=True)        # a 16-bit C cannot take atomic adds
-    assert "depth ranges" not in d("tnn", 4096, 48, 16384)                  # lanes own rows of C: no split
+    assert "depth ranges" not in d("tnn", 4096, 48, 16384)                  # enough tiles to fill the machine
+    assert "depth ranges" in d("tbn", 256, 256, 16384) and "depth ranges" in d("bnn", 512, 49, 16384)
     assert "depth ranges" not in d("tnn", 128, 128, 4608)                   # too shallow to pay for a cleared C
     assert d("tbn", 8, 50176, 4608).startswith("tbn (ternary operand on the scalar side")
     assert d("tbn", 8, 4096, 16384) == "tbn (ternary operand on the scalar side / in LDS) " \

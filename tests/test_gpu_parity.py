@@ -207,7 +207,9 @@ def test_gemm_depth_split(kind):
     C (int32 atomics).  Depths that are not multiples of 64 (eq. (6) needs the true depth of every range), ragged
     tiles, a padded ldc whose padding must stay untouched, and a C that holds garbage before the call."""
     for (M, N, K) in [(64, 64, 8192 + 70), (100, 200, 12001), (130, 257, 30000), (24, 700, 9000), (1, 64, 8192),
-                      (17, 65, 65536 + 1), (256, 256, 8192)]:
+                      (17, 65, 65536 + 1), (256, 256, 8192),
+                      # lanes own rows of C (narrow N; gemm_tbn in general): the partial results go through LDS
+                      (512, 49, 16384 + 70), (1000, 40, 20001), (70, 33, 12000), (257, 63, 10240)]:
         ldc = N + 3
         say(f"gemm_{kind} depth-split M={M} N={N} K={K} ldc={ldc}")
         A, B = synth.make_custom(kind, M, N, K, seed=M + 3 * N + K)
