@@ -224,6 +224,36 @@ LB_API int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64
                         int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * 4-bit unsigned quantized product with zero points -- the stand-in for the paper's U4 comparison algorithm (Table II,
+ * Section IV), computed as eq. (3) prescribes (one matrix product plus row-sum, column-sum and constant corrections):
+ *     C[i][j] = sum_t (A[i][t] - zA) * (B[t][j] - zB),   A, B in 0..15,  0 <= zA, zB <= 15,  int32 result.
+ * The matrix product runs on the scaled 6-bit floating-point matrix instruction of gfx950 (twice the 8-bit rate): every
+ * value v is stored as the 6-bit float v/2 with a block scale of 2, which is exact, and fp32 accumulation of the
+ * integer products is exact while 225 * K < 2^24, hence K <= 74565 (LB_EOVERFLOW beyond).
+ *
+ * Operands are packed beforehand, like the paper's reordered blocks, into the order the multiply reads them:
+ *   pack_u4   src   device, one value per byte (only the low 4 bits count); element (r, k) = src[r*stride_r + k*stride_k]
+ *                   with stride_k = 1 (A: rows = M, stride_r = lda) or stride_r = 1 (B: rows = N, stride_k = ldb),
+ *                   the same rule as pack_binary / pack_ternary
+ *             dst   device, 16-byte aligned, packed_u4_bytes(rows, K) bytes: rows padded to multiples of 32 and depth
+ *                   to multiples of 128 with zeros; fragment (row block rb, depth block kb of 64) at byte
+ *                   (rb * 2*ceil(K/128) + kb) * 1536; inside it three planes of 64 slots x 8 bytes, slot 32*h + i =
+ *                   depth positions 64*kb + 32*h .. + 31 of row 32*rb + i as a 192-bit little-endian string (position j
+ *                   in bits 6j .. 6j+5, plane p = bits 64p .. 64p+63)
+ *             sums  device, int32[rows]: sum of the K values of each row (overwritten)
+ *             Enqueues two kernels on `stream`.  rows == 0 or K == 0: nothing is written.
+ *   gemm_u4_mfma    Ap / sumA from pack_u4 of A (M strings), Bp / sumB from pack_u4 of B (N strings), same K;
+ *                   C device, int32 row-major M x N, ldc >= N, overwritten.
+ * Errors as for the other entry points (LB_EINVAL for null / misaligned pointers, bad strides, zero points outside
+ * 0..15, K < 1; LB_EOVERFLOW for K > 74565 or extents beyond 2^31 - 1).
+ */
+LB_API size_t packed_u4_bytes(int64_t rows, int64_t K);
+LB_API int pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst,
+                   int32_t *sums, void *stream);
+LB_API int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const int32_t *sumA, const void *Bp,
+                        const int32_t *sumB, int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream);
+
+/*
  * Calibration kernels for the benchmark: what the machine sustains for the two bounds of the rooflines.  The
  * caller times them (HIP events on `stream`).
  *   lb_calib_valu     runs lb_calib_valu_lane_instr(iters) lane-instructions of independent chains on registers with
@@ -247,7 +277,9 @@ LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, 
  *            4 = kernel instance of gemm_i8_mfma (0..2: 4-wave tiles 128x128, 256x256, 256x128; 3..5: wave-specialised
  *            256x128 with 3, 2, 4 depth steps of prefetch; 6: direct-to-LDS 256x128 with 64-byte depth stages;
  *            7, 8, 9: direct-to-LDS 256x128 / 128x128 / 64x64 tiles with 128-byte stages where the depth allows;
- *            an instance that cannot serve a shape falls back to the next simpler one)
+ *            an instance that cannot serve a shape falls back to the next simpler one),
+ *            5 = kernel instance of gemm_u4_mfma (0: 256x256 tile with 4 waves, 1: 256x256 with 8 waves, 2: 128x128,
+ *            3: 64x64)
  *   variant  index into that op's variant table, or -1 to restore shape-based selection.
  * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
  * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).

@@ -27,6 +27,7 @@ int fail(int code, const char *fmt, ...)
 constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K must fit
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
+constexpr int64_t kU4MaxDepth = 74565;         // 225 * K < 2^24: fp32 sums of 4-bit products stay exact
 constexpr int64_t kSkinnyMax = 32;             // widest "skinny" side served by the depth-split kernel
 constexpr int kI8Instances = 10;               // kernel instances of gemm_i8_mfma selectable through lb_set_variant
 
@@ -620,6 +621,79 @@ int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int6
     return LB_OK;
 }
 
+size_t packed_u4_bytes(int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0 || rows > kMaxExtent || K > kMaxDepth)
+        return 0;
+    const int64_t RB = (rows + 31) / 32, KB = 2 * ((K + 127) / 128);
+    return (size_t)(RB * KB * 1536);  // < 2^26 * 2^25 * 2^11
+}
+
+int pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst, int32_t *sums,
+            void *stream)
+{
+    const char *name = "pack_u4";
+    if (rows < 0 || K < 0)
+        return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
+    if (rows == 0 || K == 0)
+        return LB_OK;
+    if (!src || !dst || !sums)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (K > kU4MaxDepth || rows > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1 rows / %lld depth positions", name,
+                    (long long)rows, (long long)K, (long long)kU4MaxDepth);
+    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
+    const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
+    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
+        return fail(LB_EINVAL,
+                    "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
+                    "stride_k=%lld rows=%lld K=%lld)",
+                    name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
+    if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
+        return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
+    if (!aligned(dst, 16) || !aligned(sums, 4))
+        return fail(LB_EINVAL, "%s: dst must be 16-byte aligned, sums 4-byte aligned", name);
+    const hipError_t e = lowbit::launch_pack_u4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
+                                                static_cast<uint8_t *>(dst), sums, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const int32_t *sumA, const void *Bp,
+                 const int32_t *sumB, int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream)
+{
+    const char *name = "gemm_u4_mfma";
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    if (zA < 0 || zA > 15 || zB < 0 || zB > 15)
+        return fail(LB_EINVAL, "%s: zero points zA=%d zB=%d must lie in [0, 15]", name, zA, zB);
+    // 15 * 15 * K < 2^24 keeps every fp32 partial sum of the integer products exact
+    if (K > kU4MaxDepth)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds %lld (exact fp32 accumulation of 4-bit products)", name,
+                    (long long)K, (long long)kU4MaxDepth);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!Ap || !Bp || !sumA || !sumB || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (ldc < N)
+        return fail(LB_EINVAL, "%s: ldc=%lld < N=%lld", name, (long long)ldc, (long long)N);
+    if (ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
+    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(sumA, 4) || !aligned(sumB, 4) || !aligned(C, 4))
+        return fail(LB_EINVAL, "%s: packed operands must be 16-byte aligned, sums and C 4-byte aligned", name);
+    const hipError_t e =
+        lowbit::launch_gemm_u4(M, N, K, static_cast<const uint8_t *>(Ap), sumA, static_cast<const uint8_t *>(Bp), sumB,
+                               zA, zB, C, ldc, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
 size_t lb_calib_sink_bytes(void) { return (size_t)lowbit::calib_grid_blocks() * 2 * 256 * 4; }
 
 int64_t lb_calib_valu_lane_instr(int64_t iters) { return iters > 0 ? lowbit::calib_valu_lane_instr(iters) : 0; }
@@ -685,6 +759,12 @@ int lb_set_variant(int op, int variant)
         lowbit::i8_force_tile(variant);
         return LB_OK;
     }
+    if (op == 5) {
+        if (variant < -1 || variant >= lowbit::u4_num_instances())
+            return fail(LB_EINVAL, "lb_set_variant: 4-bit instance %d out of range", variant);
+        lowbit::u4_force_instance(variant);
+        return LB_OK;
+    }
     if (op == 3) {
         if (variant < -1 || variant >= lowbit::skinny_num_configs())
             return fail(LB_EINVAL, "lb_set_variant: skinny config %d out of range", variant);
@@ -706,6 +786,8 @@ int lb_num_variants(int op)
         return lowbit::skinny_num_configs();
     if (op == 4)
         return kI8Instances;
+    if (op == 5)
+        return lowbit::u4_num_instances();
     if (op < 0 || op > 2)
         return 0;
     lowbit::gemm_variants(op, &count);

@@ -1,0 +1,324 @@
+// 4-bit unsigned quantized GEMM with zero points on the matrix cores: the stand-in for the paper's U4 comparison
+// algorithm (Table II, Section IV; the quantized product and its zero-point expansion are eq. (2) and (3)).
+//
+// gfx950 has no 4-bit integer matrix instruction, but its scaled MFMA takes 6-bit floats (1 sign, 2 exponent, 3 mantissa
+// bits, bias 1) at twice the 8-bit rate, and with a block scale of 2 that type represents every integer 0..15 exactly
+// (0, 0.5, ..., 7.5 doubled).  Products of such values and their fp32 sums are exact while the sum stays below 2^24,
+// i.e. for K <= 74565 (15 * 15 * K < 2^24): the result is the integer product, bit for bit.
+//
+// Operand format ("fragment-major", written by pack_u4): rows padded to multiples of 32, depth to multiples of 128.
+// One fragment = 32 rows x 64 depth positions = the operand of one v_mfma_scale_f32_32x32x64_f8f6f4: lane 32*h + i of
+// the wavefront holds depth positions 32*h .. 32*h+31 of row i as 192 bits (position j in bits 6j .. 6j+5).  A fragment
+// is stored as three planes of 64 lanes x 8 bytes (plane p = bits 64p .. 64p+63 of every lane), 1536 bytes, so a wave
+// reads it with three conflict-free ds_read_b64; fragments are ordered by row block, then depth block.  Global memory
+// therefore goes to LDS as a plain contiguous copy (global_load_lds_dwordx4), with no transposes or swizzles: like the
+// paper's reordered Ablock / Bblock buffers (Section III), the packing step writes exactly what the multiply reads.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lowbit_internal.h"
+
+namespace lowbit {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kFragBytes = 1536;          // 32 rows x 64 depth positions x 6 bits
+constexpr int kSegBytes = 2 * kFragBytes; // one row block x 128 depth positions: the unit a depth stage moves
+constexpr int kScaleTwo = (int)0x80808080u;  // block scale 2^(128 - 127) in every byte, whichever the opsel picks
+
+int g_u4_forced = -1;
+
+// -------------------------------------------------------------------------------------------------- packing
+
+__global__ __launch_bounds__(256) void fill_i32_kernel(int32_t *p, int64_t n, int32_t v)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n)
+        p[i] = v;
+}
+
+// Four values 0..15 in the bytes of x -> their four 6-bit codes in the bytes of the result.
+// code(v) = 4v for v < 4, 2v + 8 for 4 <= v < 8, v + 16 from 8 on  =  4v - max(0, 2v - 8) - max(0, v - 8),
+// evaluated on all four bytes at once (no byte ever borrows from its neighbour).
+__device__ __forceinline__ uint32_t codes4(uint32_t x)
+{
+    const uint32_t ge8 = (x >> 3) & 0x01010101u;
+    const uint32_t ge4 = ((x >> 2) | (x >> 3)) & 0x01010101u;
+    const uint32_t t1 = x & (ge8 * 7u);                            // max(0, v - 8)
+    const uint32_t t2 = ((x - (ge4 << 2)) << 1) & (ge4 * 0xffu);   // max(0, 2v - 8)
+    return (x << 2) - t2 - t1;
+}
+
+// The four 6-bit codes in the bytes of c, packed into 24 bits.
+__device__ __forceinline__ uint64_t squeeze4(uint32_t c)
+{
+    return (uint64_t)((c & 0x3fu) | ((c >> 2) & 0xfc0u) | ((c >> 4) & 0x3f000u) | ((c >> 6) & 0xfc0000u));
+}
+
+// Thread (i = tid % 32, gg = tid / 32) of block (rb, chunk) encodes 32 consecutive depth positions (group g) of row
+// 32*rb + i per iteration, groups g = 8*u + gg for the units u = chunk, chunk + gridDim.y, ...: the 32 threads of
+// one gg write 256 contiguous bytes of a plane, and the eight groups of a unit cover two cache lines of every row.
+// KCONTIG: element (r, k) at src[r*stride + k]; else at src[k*stride + r].  Only the low four bits of a source byte
+// count.  The row sums are added into sums[] (cleared beforehand) with one atomic per row and block.
+template <bool KCONTIG>
+__global__ __launch_bounds__(256) void pack_u4_kernel(const uint8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                      int64_t stride, uint8_t *__restrict__ dst,
+                                                      int32_t *__restrict__ sums, int KB)
+{
+    __shared__ int red[256];
+    const int tid = threadIdx.x, i = tid & 31, gg = tid >> 5;
+    const int64_t rb = blockIdx.x, r = rb * 32 + i;
+    const int G = KB * 2, units = (G + 7) / 8;
+    const bool row_ok = r < rows;
+    uint32_t psum = 0;
+    for (int u = blockIdx.y; u < units; u += gridDim.y) {
+        const int g = u * 8 + gg;
+        if (g >= G)
+            continue;
+        const int64_t k0 = (int64_t)g * 32;
+        uint32_t w[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            w[t] = 0u;
+        if (row_ok && k0 < K) {
+            if (KCONTIG && k0 + 32 <= K) {
+                uint4 lo, hi;
+                const uint8_t *p = src + r * stride + k0;
+                __builtin_memcpy(&lo, p, 16);
+                __builtin_memcpy(&hi, p + 16, 16);
+                w[0] = lo.x; w[1] = lo.y; w[2] = lo.z; w[3] = lo.w;
+                w[4] = hi.x; w[5] = hi.y; w[6] = hi.z; w[7] = hi.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    const int64_t k = k0 + j;
+                    uint32_t v = 0u;
+                    if (k < K)
+                        v = KCONTIG ? src[r * stride + k] : src[k * stride + r];
+                    w[j >> 2] |= v << (8 * (j & 3));
+                }
+            }
+        }
+        uint64_t f[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint32_t x = w[t] & 0x0f0f0f0fu;
+            psum = __builtin_amdgcn_sad_u8(x, 0u, psum);
+            f[t] = squeeze4(codes4(x));
+        }
+        const uint64_t q0 = f[0] | (f[1] << 24) | (f[2] << 48);
+        const uint64_t q1 = (f[2] >> 16) | (f[3] << 8) | (f[4] << 32) | (f[5] << 56);
+        const uint64_t q2 = (f[5] >> 8) | (f[6] << 16) | (f[7] << 40);
+        uint8_t *o = dst + (rb * KB + (g >> 1)) * (int64_t)kFragBytes + ((g & 1) * 32 + i) * 8;
+        *reinterpret_cast<uint64_t *>(o) = q0;
+        *reinterpret_cast<uint64_t *>(o + 512) = q1;
+        *reinterpret_cast<uint64_t *>(o + 1024) = q2;
+    }
+    red[tid] = (int)psum;
+    __syncthreads();
+    if (gg == 0 && row_ok) {
+        int s = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            s += red[t * 32 + i];
+        atomicAdd(&sums[r], s);
+    }
+}
+
+// -------------------------------------------------------------------------------------------------- product
+
+// WM x WN waves, each RM x RN MFMA blocks of 32 x 32: workgroup tile (32*RM*WM) x (32*RN*WN).  Every wave both issues
+// its share of the direct-to-LDS loads (they occupy no registers) STAGES - 1 depth stages of 128 positions ahead and
+// multiplies.  One barrier per stage: before it a wave waits for its own loads of the stage about to be read; behind it
+// every wave has finished reading the stage before, whose buffer the loads issued next overwrite.
+// Row blocks beyond the operand (ragged M, N) re-read the operand's last row block: always in bounds, and the
+// products they feed are never stored.
+template <int WM, int WN, int RM, int RN, int STAGES>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
+    const uint8_t *__restrict__ Ap, const uint8_t *__restrict__ Bp, const int32_t *__restrict__ sumA,
+    const int32_t *__restrict__ sumB, int M, int N, int K, int KB2, int RBA, int RBB, int32_t *__restrict__ C,
+    int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
+{
+    constexpr int NW = WM * WN;
+    constexpr int SA = RM * WM, SB = RN * WN;          // row-block segments of A and of B per stage
+    constexpr int STAGE = (SA + SB) * kSegBytes;
+    constexpr int LOADS = (SA + SB) * 3;               // wave-wide 1 KB loads per stage
+    constexpr int LW = LOADS / NW;                     // ... per wave
+    static_assert(LOADS % NW == 0 && (STAGES - 2) * LW < 64 && STAGES >= 2, "load split / vmcnt is a 6-bit counter");
+    static_assert(STAGES * STAGE <= 160 * 1024, "LDS");
+
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[STAGES * STAGE];
+
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);   // consecutive tiles stay on one XCD (one L2)
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nMB * nNB)
+        return;
+    const int nb = idx / nMB, mb = idx - nb * nMB;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int wm = wave % WM, wn = wave / WM;
+
+    const uint8_t *src[LW];
+#pragma unroll
+    for (int t = 0; t < LW; ++t) {
+        const int q = wave * LW + t, seg = q / 3, part = q - seg * 3;
+        const uint8_t *base;
+        if (seg < SA) {
+            int rb = mb * SA + seg;
+            rb = rb < RBA ? rb : RBA - 1;
+            base = Ap + (int64_t)rb * KB2 * kSegBytes;
+        } else {
+            int cb = nb * SB + (seg - SA);
+            cb = cb < RBB ? cb : RBB - 1;
+            base = Bp + (int64_t)cb * KB2 * kSegBytes;
+        }
+        src[t] = base + part * 1024 + lane * 16;
+    }
+    auto issue = [&](int s) __attribute__((always_inline)) {
+        uint8_t *st = smem + (s % STAGES) * STAGE + wave * LW * 1024;
+#pragma unroll
+        for (int t = 0; t < LW; ++t)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src[t] + (int64_t)s * kSegBytes),
+                                             (void __attribute__((address_space(3))) *)(st + t * 1024), 16, 0, 0);
+    };
+
+    v16f acc[RM][RN];
+#pragma unroll
+    for (int i = 0; i < RM; ++i)
+#pragma unroll
+        for (int j = 0; j < RN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.f;
+
+    const int a_off = (wm * RM) * kSegBytes + lane * 8;
+    const int b_off = (SA + wn * RN) * kSegBytes + lane * 8;
+    auto frag = [&](const uint8_t *p) __attribute__((always_inline)) {
+        const uint2 q0 = *reinterpret_cast<const uint2 *>(p);
+        const uint2 q1 = *reinterpret_cast<const uint2 *>(p + 512);
+        const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 1024);
+        return v8i{(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
+    };
+    auto compute = [&](int s) __attribute__((always_inline)) {
+        const uint8_t *st = smem + (s % STAGES) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v8i a[RM], b[RN];
+#pragma unroll
+            for (int i = 0; i < RM; ++i)
+                a[i] = frag(st + a_off + i * kSegBytes + ks * kFragBytes);
+#pragma unroll
+            for (int j = 0; j < RN; ++j)
+                b[j] = frag(st + b_off + j * kSegBytes + ks * kFragBytes);
+#pragma unroll
+            for (int i = 0; i < RM; ++i)
+#pragma unroll
+                for (int j = 0; j < RN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 2, 2, 0, kScaleTwo,
+                                                                                 0, kScaleTwo);
+        }
+    };
+
+    const int nst = KB2;
+    for (int s = 0; s < STAGES - 1 && s < nst; ++s)
+        issue(s);
+    int s = 0;
+    for (; s + STAGES - 1 < nst; ++s) {
+        constexpr int vm = (STAGES - 2) * LW;  // the loads of stages s+1 .. s+STAGES-2 may stay in flight
+        __builtin_amdgcn_s_waitcnt((vm & 15) | ((vm >> 4) << 14) | 0x0f70);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        issue(s + STAGES - 1);
+        compute(s);
+    }
+    for (; s < nst; ++s) {
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): nothing further is issued
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        compute(s);
+    }
+
+    // eq. (3): sum (a - zA)(b - zB) = sum a b - zB * rowsum(A) - zA * colsum(B) + K zA zB
+    const int m0 = mb * 32 * SA, n0 = nb * 32 * SB;
+    const int kzz = K * zA * zB;
+#pragma unroll
+    for (int j = 0; j < RN; ++j) {
+        const int col = n0 + (wn * RN + j) * 32 + (lane & 31);
+        const bool col_ok = col < N;
+        const int ccorr = kzz - (col_ok ? zA * sumB[col] : 0);
+#pragma unroll
+        for (int i = 0; i < RM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + (wm * RM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (col_ok && row < M)
+                    C[(int64_t)row * ldc + col] = (int)acc[i][j][r] + ccorr - zB * sumA[row];
+            }
+    }
+}
+
+template <int WM, int WN, int RM, int RN, int STAGES>
+hipError_t launch_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
+                     const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
+{
+    constexpr int BM = 32 * RM * WM, BN = 32 * RN * WN;
+    const int64_t nMB = (M + BM - 1) / BM, nNB = (N + BN - 1) / BN;
+    const int64_t tiles = nMB * nNB;
+    const int64_t tiles_per_xcd = (tiles + 7) / 8;
+    if (tiles_per_xcd * 8 > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((gemm_u4_fp6_kernel<WM, WN, RM, RN, STAGES>), dim3((unsigned)(tiles_per_xcd * 8)),
+                       dim3(64 * WM * WN), 0, stream, Ap, Bp, sumA, sumB, (int)M, (int)N, (int)K,
+                       (int)((K + 127) / 128), (int)((M + 31) / 32), (int)((N + 31) / 32), C, ldc, (int)nMB, (int)nNB,
+                       (int)tiles_per_xcd, zA, zB);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int u4_num_instances() { return 4; }
+void u4_force_instance(int t) { g_u4_forced = t; }
+
+hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
+                          uint8_t *dst, int32_t *sums, hipStream_t stream)
+{
+    const int64_t RB = (rows + 31) / 32;
+    const int KB = 2 * (int)((K + 127) / 128);
+    if (RB > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream, sums, rows, 0);
+    // about 4096 blocks at least, each looping over its share of the depth
+    const int units = (KB * 2 + 7) / 8;
+    int64_t chunks = (4096 + RB - 1) / RB;
+    chunks = chunks < 1 ? 1 : chunks > units ? units : chunks;
+    const dim3 grid((unsigned)RB, (unsigned)chunks);
+    if (stride_k == 1)
+        hipLaunchKernelGGL((pack_u4_kernel<true>), grid, dim3(256), 0, stream, src, rows, K, stride_r, dst, sums, KB);
+    else
+        hipLaunchKernelGGL((pack_u4_kernel<false>), grid, dim3(256), 0, stream, src, rows, K, stride_k, dst, sums, KB);
+    return hipGetLastError();
+}
+
+// Instances: 0 = 256 x 256 tile (4 waves of 128 x 128), 1 = 256 x 256 (8 waves of 64 x 128), 2 = 128 x 128 (4 waves of
+// 64 x 64), 3 = 64 x 64 (4 waves of 32 x 32, 4 stages).
+hipError_t launch_gemm_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
+                          const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
+{
+    int inst = g_u4_forced;
+    if (inst < 0) {
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+        inst = t256 >= 192 ? 0 : t128 >= 128 ? 2 : 3;
+    }
+    switch (inst) {
+    case 0: return launch_u4<2, 2, 4, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 1: return launch_u4<4, 2, 2, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 2: return launch_u4<2, 2, 2, 2, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    default: return launch_u4<2, 2, 1, 1, 4>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    }
+}
+
+}  // namespace lowbit

@@ -120,6 +120,31 @@ def test_u8_argument_validation(L):
     assert f(0, 4, 16, None, 16, None, 4, 0, 0, None, 4, None) == binding.LB_OK
 
 
+def test_u4_argument_validation(L):
+    fake = 0x1000
+    assert L.packed_u4_bytes(1, 1) == 2 * 1536
+    assert L.packed_u4_bytes(33, 129) == 2 * 4 * 1536
+    assert L.packed_u4_bytes(1024, 4608) == 32 * 72 * 1536
+    assert L.packed_u4_bytes(0, 5) == 0 and L.packed_u4_bytes(-1, 5) == 0
+    p = L.pack_u4
+    assert p(None, 4, 64, 64, 1, fake, fake, None) == binding.LB_EINVAL                      # null source
+    assert p(fake, 4, 64, 32, 1, fake, fake, None) == binding.LB_EINVAL                      # stride_r < K
+    assert p(fake, 4, 64, 2, 2, fake, fake, None) == binding.LB_EINVAL                       # neither stride is 1
+    assert p(fake, 4, 64, 64, 1, fake + 8, fake, None) == binding.LB_EINVAL                  # dst misaligned
+    assert p(fake, 4, 74566, 74566, 1, fake, fake, None) == binding.LB_EOVERFLOW
+    assert p(None, 0, 64, 64, 1, None, None, None) == binding.LB_OK
+    g = L.gemm_u4_mfma
+    assert g(4, 4, 64, fake, fake, fake, fake, 16, 0, fake, 4, None) == binding.LB_EINVAL    # zero point out of range
+    assert g(4, 4, 64, fake, fake, fake, fake, 0, -1, fake, 4, None) == binding.LB_EINVAL
+    assert g(4, 4, 0, fake, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL
+    assert g(4, 4, 74566, fake, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EOVERFLOW
+    assert b"74565" in L.lb_last_error()
+    assert g(4, 4, 64, fake, None, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL     # null sums
+    assert g(4, 4, 64, fake, fake, fake, fake, 0, 0, fake, 3, None) == binding.LB_EINVAL     # ldc < N
+    assert g(4, 4, 64, fake + 4, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL  # Ap misaligned
+    assert g(0, 4, 64, None, None, None, None, 0, 0, None, 4, None) == binding.LB_OK
+
+
 def test_requant_argument_validation(L):
     fake = 0x1000
     f = L.gemm_requant
@@ -159,7 +184,9 @@ def test_variant_hooks(L):
     assert L.lb_set_variant(3, L.lb_num_variants(3)) == binding.LB_EINVAL
     assert L.lb_set_variant(4, 0) == binding.LB_OK and L.lb_set_variant(4, -1) == binding.LB_OK
     assert L.lb_set_variant(4, L.lb_num_variants(4)) == binding.LB_EINVAL
-    assert L.lb_set_variant(5, 0) == binding.LB_EINVAL
+    assert L.lb_set_variant(5, 0) == binding.LB_OK and L.lb_set_variant(5, -1) == binding.LB_OK
+    assert L.lb_set_variant(5, L.lb_num_variants(5)) == binding.LB_EINVAL
+    assert L.lb_set_variant(6, 0) == binding.LB_EINVAL
     assert L.lb_num_variants(7) == 0
 
 
