@@ -346,7 +346,16 @@ def main() -> int:
         uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)      # {-1,0,1} -> {0,1,2}, zero point 1
         tu8 = dev_time(lambda: lb.gemm_u8_mfma(M, N, K, uA, K, uB, N, 1, 1, C, N), 20)
         extra["u8_zero_point_mfma_tops"] = w.ops / tu8 / 1e12
-        del uA, uB
+        # 4-bit stand-in for the paper's U4: the same values ({0,1,2}, zero point 1) packed as 6-bit floats in
+        # matrix-core fragment order, multiplied on the scaled 6-bit float matrix instruction
+        uAp, usA = lb.pack_u4(uA, M, K, K, 1)
+        uBp, usB = lb.pack_u4(uB, N, K, 1, N)
+        tu4 = dev_time(lambda: lb.gemm_u4_mfma(M, N, K, uAp, usA, uBp, usB, 1, 1, C, N), 20)
+        tu4pb = dev_time(lambda: lb.pack_u4(uB, N, K, 1, N, uBp, usB), 10)
+        extra["u4_fp6_mfma"] = {"gemm_tops": w.ops / tu4 / 1e12, "gemm_ms": tu4 * 1e3, "pack_b_ms": tu4pb * 1e3,
+                                "frac_of_fp6_mfma_peak": w.ops / tu4 / 10.1e15,
+                                "speedup_vs_int8_mfma": ti8 / tu4, "gemm_tnn_speed_relative": tu4 / gemm_s}
+        del uA, uB, uAp, usA, uBp, usB
         # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
         try:
             torch._int_mm(dA, dB)

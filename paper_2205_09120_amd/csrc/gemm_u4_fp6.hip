@@ -15,6 +15,7 @@
 // paper's reordered Ablock / Bblock buffers (Section III), the packing step writes exactly what the multiply reads.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "lowbit_internal.h"
 
@@ -176,12 +177,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
         }
         src[t] = base + part * 1024 + lane * 16;
     }
+    // The direct-to-LDS loads are inline assembly: the compiler would otherwise order every LDS read behind ALL
+    // outstanding direct loads (vmcnt(0)), which serialises the ring of stages.  Written this way it does not know
+    // that these loads write LDS; what orders them against the fragment reads is the stage barrier, which follows each
+    // wave's own explicit vmcnt wait.  M0 carries the LDS address of a wave-wide load (lane l lands at M0 + 16*l).
+    auto issue_one = [&](int s, int t) __attribute__((always_inline)) {
+        const uint32_t st = (uint32_t)(uintptr_t)smem + (uint32_t)((s % STAGES) * STAGE + (wave * LW + t) * 1024);
+        const uint8_t *g = src[t] + (int64_t)s * kSegBytes;
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(st), "v"(g) : "memory", "m0");
+    };
     auto issue = [&](int s) __attribute__((always_inline)) {
-        uint8_t *st = smem + (s % STAGES) * STAGE + wave * LW * 1024;
 #pragma unroll
         for (int t = 0; t < LW; ++t)
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src[t] + (int64_t)s * kSegBytes),
-                                             (void __attribute__((address_space(3))) *)(st + t * 1024), 16, 0, 0);
+            issue_one(s, t);
     };
 
     v16f acc[RM][RN];
@@ -193,6 +201,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.f;
 
+    // Fragments of the next depth step are read while the MFMAs of the current one run (two fragment sets alternate).
     const int a_off = (wm * RM) * kSegBytes + lane * 8;
     const int b_off = (SA + wn * RN) * kSegBytes + lane * 8;
     auto frag = [&](const uint8_t *p) __attribute__((always_inline)) {
@@ -201,62 +210,135 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
         const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 1024);
         return v8i{(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
     };
-    auto compute = [&](int s) __attribute__((always_inline)) {
-        const uint8_t *st = smem + (s % STAGES) * STAGE;
+    auto read_frags = [&](int s, int ks, v8i(&a)[RM], v8i(&b)[RN]) __attribute__((always_inline)) {
+        const uint8_t *st = smem + (s % STAGES) * STAGE + ks * kFragBytes;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v8i a[RM], b[RN];
+        for (int i = 0; i < RM; ++i)
+            a[i] = frag(st + a_off + i * kSegBytes);
 #pragma unroll
-            for (int i = 0; i < RM; ++i)
-                a[i] = frag(st + a_off + i * kSegBytes + ks * kFragBytes);
+        for (int j = 0; j < RN; ++j)
+            b[j] = frag(st + b_off + j * kSegBytes);
+    };
+    auto mfma_rows = [&](v8i(&a)[RM], v8i(&b)[RN], int i0, int i1) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
 #pragma unroll
             for (int j = 0; j < RN; ++j)
-                b[j] = frag(st + b_off + j * kSegBytes + ks * kFragBytes);
-#pragma unroll
-            for (int i = 0; i < RM; ++i)
-#pragma unroll
-                for (int j = 0; j < RN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 2, 2, 0, kScaleTwo,
-                                                                                 0, kScaleTwo);
-        }
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 2, 2, 0, kScaleTwo, 0,
+                                                                             kScaleTwo);
     };
-
-    const int nst = KB2;
-    for (int s = 0; s < STAGES - 1 && s < nst; ++s)
-        issue(s);
-    int s = 0;
-    for (; s + STAGES - 1 < nst; ++s) {
-        constexpr int vm = (STAGES - 2) * LW;  // the loads of stages s+1 .. s+STAGES-2 may stay in flight
+    // "stage s holds its data and the stage before it is free": own loads landed (all but `in_flight` newer ones),
+    // then the workgroup barrier
+    auto stage_barrier = [&](auto in_flight) __attribute__((always_inline)) {
+        constexpr int vm = decltype(in_flight)::value;
+        static_assert(vm < 64, "vmcnt is a 6-bit counter");
         __builtin_amdgcn_s_waitcnt((vm & 15) | ((vm >> 4) << 14) | 0x0f70);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        issue(s + STAGES - 1);
-        compute(s);
+    };
+    using steady = std::integral_constant<int, (STAGES - 2) * LW>;
+    using drain = std::integral_constant<int, 0>;
+
+    // One stage = two depth steps.  What happens at the switch to stage s + 1 depends on how many stages are left
+    // (stages up to s + STAGES - 1 have been issued by then): MODE 0 barrier with STAGES - 2 stages in flight, then
+    // issue stage s + STAGES; 1 the same barrier, nothing left to issue; 2 barrier with everything landed; 3 last
+    // stage, no switch.  Each mode is straight-line code, so that the order written here is the order executed.
+    const int nst = KB2;
+    v8i fa[2][RM], fb[2][RN];
+    for (int s = 0; s < STAGES - 1 && s < nst; ++s)
+        issue(s);
+    if (STAGES - 1 < nst) {
+        stage_barrier(steady{});
+        issue(STAGES - 1);
+    } else {
+        stage_barrier(drain{});
     }
-    for (; s < nst; ++s) {
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): nothing further is issued
+    read_frags(0, 0, fa[0], fb[0]);
+    // Per depth step: the first row of MFMAs (the compiler's wait in front of it covers the fragment reads in
+    // flight), the reads of the next step -- behind the stage barrier when the step is the last of its stage --, the
+    // other rows.
+    auto stage_body = [&](auto mode, int s) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode)::value;
+        mfma_rows(fa[0], fb[0], 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_barrier" ::: "memory");
+        read_frags(s, 1, fa[1], fb[1]);
         __builtin_amdgcn_sched_barrier(0);
-        compute(s);
+        mfma_rows(fa[0], fb[0], 1, RM);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_rows(fa[1], fb[1], 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MODE == 0 || MODE == 1) {
+            stage_barrier(steady{});
+        } else if constexpr (MODE == 2) {
+            stage_barrier(drain{});
+        }
+        if constexpr (MODE != 3)
+            read_frags(s + 1, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MODE == 0 && RM > 1) {
+            // the direct loads of stage s + STAGES go out between the remaining MFMAs, not in one burst: a wave
+            // that is busy issuing loads issues no MFMAs
+            constexpr int SLOTS = RM > 1 ? (RM - 1) * RN : 1, PER = (LW + SLOTS - 1) / SLOTS;
+#pragma unroll
+            for (int i = 1; i < RM; ++i)
+#pragma unroll
+                for (int j = 0; j < RN; ++j) {
+#pragma unroll
+                    for (int c = 0; c < PER; ++c) {
+                        const int t = ((i - 1) * RN + j) * PER + c;
+                        if (t < LW)
+                            issue_one(s + STAGES, t);
+                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[1][i], fb[1][j], acc[i][j], 2, 2, 0,
+                                                                                 kScaleTwo, 0, kScaleTwo);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        } else {
+            if constexpr (MODE == 0)
+                issue(s + STAGES);
+            mfma_rows(fa[1], fb[1], 1, RM);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    {
+        int s = 0;
+        for (; s + STAGES < nst; ++s)
+            stage_body(std::integral_constant<int, 0>{}, s);
+        if (s + STAGES == nst) {
+            stage_body(std::integral_constant<int, 1>{}, s);
+            ++s;
+        }
+        for (; s + 1 < nst; ++s)
+            stage_body(std::integral_constant<int, 2>{}, s);
+        stage_body(std::integral_constant<int, 3>{}, s);
     }
 
-    // eq. (3): sum (a - zA)(b - zB) = sum a b - zB * rowsum(A) - zA * colsum(B) + K zA zB
+    // eq. (3): sum (a - zA)(b - zB) = sum a b - zB * rowsum(A) - zA * colsum(B) + K zA zB.
+    // The row sums of all the rows a lane stores to are fetched up front, from indices clamped into range, so that
+    // the loads go out together instead of one in front of every guarded store.
     const int m0 = mb * 32 * SA, n0 = nb * 32 * SB;
     const int kzz = K * zA * zB;
+    int rcorr[RM][16];
+#pragma unroll
+    for (int i = 0; i < RM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + (wm * RM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            rcorr[i][r] = zB * sumA[row < M ? row : M - 1];
+        }
 #pragma unroll
     for (int j = 0; j < RN; ++j) {
         const int col = n0 + (wn * RN + j) * 32 + (lane & 31);
         const bool col_ok = col < N;
-        const int ccorr = kzz - (col_ok ? zA * sumB[col] : 0);
+        const int ccorr = kzz - zA * sumB[col_ok ? col : N - 1];
 #pragma unroll
         for (int i = 0; i < RM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + (wm * RM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (col_ok && row < M)
-                    C[(int64_t)row * ldc + col] = (int)acc[i][j][r] + ccorr - zB * sumA[row];
+                    C[(int64_t)row * ldc + col] = (int)acc[i][j][r] + ccorr - rcorr[i][r];
             }
     }
 }
@@ -311,7 +393,7 @@ hipError_t launch_gemm_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, co
     int inst = g_u4_forced;
     if (inst < 0) {
         const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
-        inst = t256 >= 192 ? 0 : t128 >= 128 ? 2 : 3;
+        inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
     }
     switch (inst) {
     case 0: return launch_u4<2, 2, 4, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
