@@ -58,12 +58,26 @@ __device__ __forceinline__ uint64_t squeeze4(uint32_t c)
     return (uint64_t)((c & 0x3fu) | ((c >> 2) & 0xfc0u) | ((c >> 4) & 0x3f000u) | ((c >> 6) & 0xfc0000u));
 }
 
+// 32 values (four per dword, low nibbles) -> the 192-bit string of their codes; their sum is added to `sum`.
+__device__ __forceinline__ void encode32(const uint32_t (&w)[8], uint64_t &q0, uint64_t &q1, uint64_t &q2, uint32_t &sum)
+{
+    uint64_t f[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t x = w[t] & 0x0f0f0f0fu;
+        sum = __builtin_amdgcn_sad_u8(x, 0u, sum);
+        f[t] = squeeze4(codes4(x));
+    }
+    q0 = f[0] | (f[1] << 24) | (f[2] << 48);
+    q1 = (f[2] >> 16) | (f[3] << 8) | (f[4] << 32) | (f[5] << 56);
+    q2 = (f[5] >> 8) | (f[6] << 16) | (f[7] << 40);
+}
+
 // Thread (i = tid % 32, gg = tid / 32) of block (rb, chunk) encodes 32 consecutive depth positions (group g) of row
 // 32*rb + i per iteration, groups g = 8*u + gg for the units u = chunk, chunk + gridDim.y, ...: the 32 threads of
 // one gg write 256 contiguous bytes of a plane, and the eight groups of a unit cover two cache lines of every row.
-// KCONTIG: element (r, k) at src[r*stride + k]; else at src[k*stride + r].  Only the low four bits of a source byte
-// count.  The row sums are added into sums[] (cleared beforehand) with one atomic per row and block.
-template <bool KCONTIG>
+// Depth-contiguous source: element (r, k) at src[r*stride + k].  Only the low four bits of a source byte count.  The
+// row sums are added into sums[] (cleared beforehand) with one atomic per row and block.
 __global__ __launch_bounds__(256) void pack_u4_kernel(const uint8_t *__restrict__ src, int64_t rows, int64_t K,
                                                       int64_t stride, uint8_t *__restrict__ dst,
                                                       int32_t *__restrict__ sums, int KB)
@@ -84,7 +98,7 @@ __global__ __launch_bounds__(256) void pack_u4_kernel(const uint8_t *__restrict_
         for (int t = 0; t < 8; ++t)
             w[t] = 0u;
         if (row_ok && k0 < K) {
-            if (KCONTIG && k0 + 32 <= K) {
+            if (k0 + 32 <= K) {
                 uint4 lo, hi;
                 const uint8_t *p = src + r * stride + k0;
                 __builtin_memcpy(&lo, p, 16);
@@ -97,21 +111,13 @@ __global__ __launch_bounds__(256) void pack_u4_kernel(const uint8_t *__restrict_
                     const int64_t k = k0 + j;
                     uint32_t v = 0u;
                     if (k < K)
-                        v = KCONTIG ? src[r * stride + k] : src[k * stride + r];
+                        v = src[r * stride + k];
                     w[j >> 2] |= v << (8 * (j & 3));
                 }
             }
         }
-        uint64_t f[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const uint32_t x = w[t] & 0x0f0f0f0fu;
-            psum = __builtin_amdgcn_sad_u8(x, 0u, psum);
-            f[t] = squeeze4(codes4(x));
-        }
-        const uint64_t q0 = f[0] | (f[1] << 24) | (f[2] << 48);
-        const uint64_t q1 = (f[2] >> 16) | (f[3] << 8) | (f[4] << 32) | (f[5] << 56);
-        const uint64_t q2 = (f[5] >> 8) | (f[6] << 16) | (f[7] << 40);
+        uint64_t q0, q1, q2;
+        encode32(w, q0, q1, q2, psum);
         uint8_t *o = dst + (rb * KB + (g >> 1)) * (int64_t)kFragBytes + ((g & 1) * 32 + i) * 8;
         *reinterpret_cast<uint64_t *>(o) = q0;
         *reinterpret_cast<uint64_t *>(o + 512) = q1;
@@ -125,6 +131,82 @@ __global__ __launch_bounds__(256) void pack_u4_kernel(const uint8_t *__restrict_
         for (int t = 0; t < 8; ++t)
             s += red[t * 32 + i];
         atomicAdd(&sums[r], s);
+    }
+}
+
+// Depth-strided source (element (r, k) at src[k*stride + r], the K x rows layout of a right operand): a block covers
+// 128 rows; lane (q = lane % 32, hh = lane / 32) of wave w loads, for each of the 32 depth positions of group
+// g = 8*u + 2*w + hh, the four bytes of rows 4q .. 4q+3 -- 32 lanes read one whole 128-byte line of a depth row --,
+// transposes the 4 x 32 bytes in registers (4 x 4 byte transposes, v_perm_b32) and encodes its four rows.  Their four
+// 8-byte pieces of a plane are adjacent slots: 32-byte stores, 256 contiguous bytes per eight lanes.
+__global__ __launch_bounds__(256) void pack_u4_strided_kernel(const uint8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                              int64_t stride, uint8_t *__restrict__ dst,
+                                                              int32_t *__restrict__ sums, int KB, int64_t RB)
+{
+    __shared__ int red[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane & 31, hh = lane >> 5;
+    const int64_t r0 = (int64_t)blockIdx.x * 128 + 4 * q;
+    const int64_t rb = r0 >> 5;
+    const int G = KB * 2, units = (G + 7) / 8;
+    const bool quad_ok = r0 + 3 < rows;
+    uint32_t psum[4] = {0u, 0u, 0u, 0u};
+    for (int u = blockIdx.y; u < units; u += gridDim.y) {
+        const int g = u * 8 + wave * 2 + hh;
+        if (g >= G || rb >= RB)
+            continue;
+        const int64_t k0 = (int64_t)g * 32;
+        uint32_t w[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int64_t k = k0 + j;
+            uint32_t v = 0u;
+            if (k < K) {
+                const uint8_t *p = src + k * stride + r0;
+                if (quad_ok) {
+                    __builtin_memcpy(&v, p, 4);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (r0 + b < rows)
+                            v |= (uint32_t)p[b] << (8 * b);
+                }
+            }
+            w[j] = v;
+        }
+        uint64_t out[3][4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            uint32_t x[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                // byte rr of w[4t .. 4t+3]: two rounds of byte interleaving
+                const uint32_t a = __builtin_amdgcn_perm(w[4 * t + 1], w[4 * t], rr < 2 ? 0x05010400u : 0x07030602u);
+                const uint32_t b = __builtin_amdgcn_perm(w[4 * t + 3], w[4 * t + 2], rr < 2 ? 0x05010400u : 0x07030602u);
+                x[t] = __builtin_amdgcn_perm(b, a, (rr & 1) ? 0x07060302u : 0x05040100u);
+            }
+            encode32(x, out[0][rr], out[1][rr], out[2][rr], psum[rr]);
+        }
+        uint8_t *o = dst + (rb * KB + (g >> 1)) * (int64_t)kFragBytes + ((g & 1) * 32 + 4 * (q & 7)) * 8;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            *reinterpret_cast<ulonglong2 *>(o + p * 512) = make_ulonglong2(out[p][0], out[p][1]);
+            *reinterpret_cast<ulonglong2 *>(o + p * 512 + 16) = make_ulonglong2(out[p][2], out[p][3]);
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+        red[rr][tid] = (int)psum[rr];
+    __syncthreads();
+    if (tid < 32) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            int s = 0;
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                s += red[rr][t * 32 + q];
+            if (r0 + rr < rows)
+                atomicAdd(&sums[r0 + rr], s);
+        }
     }
 }
 
@@ -378,10 +460,15 @@ hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t s
     int64_t chunks = (4096 + RB - 1) / RB;
     chunks = chunks < 1 ? 1 : chunks > units ? units : chunks;
     const dim3 grid((unsigned)RB, (unsigned)chunks);
-    if (stride_k == 1)
-        hipLaunchKernelGGL((pack_u4_kernel<true>), grid, dim3(256), 0, stream, src, rows, K, stride_r, dst, sums, KB);
-    else
-        hipLaunchKernelGGL((pack_u4_kernel<false>), grid, dim3(256), 0, stream, src, rows, K, stride_k, dst, sums, KB);
+    if (stride_k == 1) {
+        hipLaunchKernelGGL(pack_u4_kernel, grid, dim3(256), 0, stream, src, rows, K, stride_r, dst, sums, KB);
+    } else {
+        const int64_t RB4 = (rows + 127) / 128;
+        int64_t ch = (4096 + RB4 - 1) / RB4;
+        ch = ch < 1 ? 1 : ch > units ? units : ch;
+        hipLaunchKernelGGL(pack_u4_strided_kernel, dim3((unsigned)RB4, (unsigned)ch), dim3(256), 0, stream, src, rows, K,
+                           stride_k, dst, sums, KB, RB);
+    }
     return hipGetLastError();
 }
 
