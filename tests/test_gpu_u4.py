@@ -110,3 +110,87 @@ def test_gemm_u4_headline_shape_sampled():
     assert np.array_equal(C[ii, jj], oracle.gemm_samples(As, Bs, ii, jj))
     cols = slice(50176 - 300, 50176)
     assert np.array_equal(C[:64, cols], oracle.gemm(np.ascontiguousarray(As[:64]), np.ascontiguousarray(Bs[:, cols])))
+
+
+def test_u4_random_sweep():
+    """Seeded random shapes, instances, zero points, leading dimensions and source layouts."""
+    rng = np.random.default_rng(2024)
+    try:
+        for n in range(1, 161):
+            r = rng.random()
+            if r < 0.2:
+                M, N, K = int(rng.integers(1, 40)), int(np.exp(rng.uniform(0, np.log(3000)))), int(np.exp(rng.uniform(0, np.log(20000))))
+            elif r < 0.4:
+                M, N, K = int(np.exp(rng.uniform(0, np.log(3000)))), int(rng.integers(1, 40)), int(np.exp(rng.uniform(0, np.log(20000))))
+            else:
+                M, N, K = (int(np.exp(rng.uniform(0, np.log(1200)))) for _ in range(3))
+            inst = int(rng.integers(-1, lb.lb_num_variants(5)))
+            zA, zB = int(rng.integers(0, 16)), int(rng.integers(0, 16))
+            lda, ldb, ldc = K + int(rng.choice([0, 1, 16, 5])), N + int(rng.choice([0, 1, 4, 7])), N + int(rng.choice([0, 3]))
+            a_strided = bool(rng.integers(0, 2))          # A handed over as K x M (depth-strided) instead
+            print(f"[{n}] u4 M={M} N={N} K={K} inst={inst} z=({zA},{zB}) lda={lda} ldb={ldb} ldc={ldc} a_strided={a_strided}",
+                  flush=True)
+            A = rng.integers(0, 16, size=(M, K), dtype=np.uint8)
+            B = rng.integers(0, 16, size=(K, N), dtype=np.uint8)
+            bufB = np.full((K, ldb), 9, dtype=np.uint8)
+            bufB[:, :N] = B
+            if a_strided:
+                bufA = np.full((K, M + 3), 7, dtype=np.uint8)
+                bufA[:, :M] = A.T
+                Ap, sA = lb.pack_u4(torch.from_numpy(bufA).cuda(), M, K, 1, M + 3)
+            else:
+                bufA = np.full((M, lda), 7, dtype=np.uint8)
+                bufA[:, :K] = A
+                Ap, sA = lb.pack_u4(torch.from_numpy(bufA).cuda(), M, K, lda, 1)
+            Bp, sB = lb.pack_u4(torch.from_numpy(bufB).cuda(), N, K, 1, ldb)
+            if M * K <= 60000:
+                want_p, want_s = u4ref.pack_u4(A)
+                assert np.array_equal(Ap.cpu().numpy(), want_p) and np.array_equal(sA.cpu().numpy(), want_s), n
+            C = torch.full((M, ldc), 99, dtype=torch.int32, device="cuda")
+            lb.lb_set_variant(5, inst)
+            lb.gemm_u4_mfma(M, N, K, Ap, sA, Bp, sB, zA, zB, C, ldc)
+            lb.lb_set_variant(5, -1)
+            got = C.cpu().numpy()
+            assert np.array_equal(got[:, :N], oracle.gemm_u8_zero_point(A, B, zA, zB)), n
+            assert (got[:, N:] == 99).all(), n
+    finally:
+        lb.lb_set_variant(5, -1)
+
+
+def test_u4_captured_in_a_graph_replays_exactly():
+    """pack_u4 (which clears the row sums with a fill kernel, not a memset) and gemm_u4_mfma only enqueue kernels:
+    captured once, replayed with new inputs and eager work in between, every replay checked against the oracle."""
+    M, N, K = 150, 300, 700
+    dA = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
+    dB = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    Ap = torch.empty(lb.packed_u4_bytes(M, K), dtype=torch.uint8, device="cuda")
+    Bp = torch.empty(lb.packed_u4_bytes(N, K), dtype=torch.uint8, device="cuda")
+    sA = torch.empty(M, dtype=torch.int32, device="cuda")
+    sB = torch.empty(N, dtype=torch.int32, device="cuda")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+
+    def pipeline():
+        lb.pack_u4(dA, M, K, K, 1, Ap, sA)
+        lb.pack_u4(dB, N, K, 1, N, Bp, sB)
+        lb.gemm_u4_mfma(M, N, K, Ap, sA, Bp, sB, 5, 9, C, N)
+
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        pipeline()
+    torch.cuda.current_stream().wait_stream(st)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        pipeline()
+    for rep in range(4):
+        A, B = _draw(500 + rep, M, N, K)
+        dA.copy_(torch.from_numpy(A))
+        dB.copy_(torch.from_numpy(B))
+        C.fill_(-1)
+        sA.fill_(123)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), oracle.gemm_u8_zero_point(A, B, 5, 9)), rep
+        assert np.array_equal(sA.cpu().numpy(), A.sum(axis=1, dtype=np.int64).astype(np.int32)), rep
