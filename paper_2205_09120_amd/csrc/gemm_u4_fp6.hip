@@ -266,7 +266,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
     auto issue_one = [&](int s, int t) __attribute__((always_inline)) {
         const uint32_t st = (uint32_t)(uintptr_t)smem + (uint32_t)((s % STAGES) * STAGE + (wave * LW + t) * 1024);
         const uint8_t *g = src[t] + (int64_t)s * kSegBytes;
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(st), "v"(g) : "memory", "m0");
+        // one wait state between the write of M0 and the load that reads it (the compiler inserts it for its own
+        // direct loads; it does not look into assembly statements)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(st), "v"(g) : "memory", "m0");
     };
     auto issue = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
