@@ -254,6 +254,28 @@ LB_API int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const i
                         const int32_t *sumB, int32_t zA, int32_t zB, int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * The paper's product C = A B over {-1, 0, +1} (Section II-A; value sets of Section III-A: any mix of ternary and
+ * binary operands) on the matrix cores instead of AND / XOR / popcount: both operands stored as 4-bit floats (1 sign,
+ * 2 exponent, 1 mantissa bit, bias 1; 0 and +-1 are exact), multiplied by the scaled low-precision matrix instruction of
+ * gfx950 with fp32 accumulation, which is exact while |C| <= K < 2^24 (LB_EOVERFLOW beyond).  Not the paper's algorithm:
+ * the point of comparison for it on hardware that has 4-bit matrix arithmetic.  4 bits per value instead of 2 or 1.
+ *   pack_t4       src   device, int8, taken by sign like pack_ternary (x > 0 -> +1, x < 0 -> -1); element (r, k) =
+ *                       src[r*stride_r + k*stride_k] with stride_k = 1 or stride_r = 1 (same rule as pack_ternary)
+ *                 dst   device, 16-byte aligned, packed_t4_bytes(rows, K) bytes: rows padded to multiples of 32, depth
+ *                       to multiples of 128 with zeros; fragment (row block rb, depth block kb of 64) at byte
+ *                       (rb * 2*ceil(K/128) + kb) * 1024; inside it 64 slots of 16 bytes, slot 32*h + i = depth positions
+ *                       64*kb + 32*h .. + 31 of row 32*rb + i, position j in bits 4j .. 4j+3 (little-endian)
+ *   gemm_t4_mfma  Ap from pack_t4 of A (M strings), Bp from pack_t4 of B (N strings), same K; C device, int32
+ *                 row-major M x N, ldc >= N, overwritten.
+ * Errors as for the other entry points.
+ */
+LB_API size_t packed_t4_bytes(int64_t rows, int64_t K);
+LB_API int pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst,
+                   void *stream);
+LB_API int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const void *Bp, int32_t *C, int64_t ldc,
+                        void *stream);
+
+/*
  * Calibration kernels for the benchmark: what the machine sustains for the two bounds of the rooflines.  The
  * caller times them (HIP events on `stream`).
  *   lb_calib_valu     runs lb_calib_valu_lane_instr(iters) lane-instructions of independent chains on registers with
@@ -278,8 +300,8 @@ LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, 
  *            256x128 with 3, 2, 4 depth steps of prefetch; 6: direct-to-LDS 256x128 with 64-byte depth stages;
  *            7, 8, 9: direct-to-LDS 256x128 / 128x128 / 64x64 tiles with 128-byte stages where the depth allows;
  *            an instance that cannot serve a shape falls back to the next simpler one),
- *            5 = kernel instance of gemm_u4_mfma (0: 256x256 tile with 4 waves, 1: 256x256 with 8 waves, 2: 128x128,
- *            3: 64x64)
+ *            5 = kernel instance of gemm_u4_mfma and gemm_t4_mfma (0: 256x256 tile with 4 waves, 1: 256x256 with 8
+ *            waves, 2: 128x128, 3: 64x64)
  *   variant  index into that op's variant table, or -1 to restore shape-based selection.
  * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
  * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).

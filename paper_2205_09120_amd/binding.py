@@ -21,7 +21,7 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
-           "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "lb_set_variant", "lb_num_variants",
+           "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_describe_plan", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
 
@@ -84,6 +84,12 @@ def lib() -> ctypes.CDLL:
         L.pack_u4.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp]
         L.gemm_u4_mfma.restype = ci
         L.gemm_u4_mfma.argtypes = [i64, i64, i64, vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, vp, i64, vp]
+        L.packed_t4_bytes.restype = ctypes.c_size_t
+        L.packed_t4_bytes.argtypes = [i64, i64]
+        L.pack_t4.restype = ci
+        L.pack_t4.argtypes = [vp, i64, i64, i64, i64, vp, vp]
+        L.gemm_t4_mfma.restype = ci
+        L.gemm_t4_mfma.argtypes = [i64, i64, i64, vp, vp, vp, i64, vp]
         L.lb_calib_sink_bytes.restype = ctypes.c_size_t
         L.lb_calib_sink_bytes.argtypes = []
         L.lb_calib_valu_lane_instr.restype = i64
@@ -286,6 +292,30 @@ def gemm_u4_mfma(M, N, K, Ap, sumA, Bp, sumB, zA: int, zB: int, C=None, ldc=None
         ldc = C.stride(0)
     _check(lib().gemm_u4_mfma(M, N, K, _ptr(Ap), _ptr(sumA), _ptr(Bp), _ptr(sumB), zA, zB, _ptr(C), ldc,
                               _stream(stream)))
+    return C
+
+
+def packed_t4_bytes(rows: int, K: int) -> int:
+    return lib().packed_t4_bytes(rows, K)
+
+
+def pack_t4(src: torch.Tensor, rows: int, K: int, stride_r: int, stride_k: int, dst: Optional[torch.Tensor] = None,
+            stream=None) -> torch.Tensor:
+    """Ternary / binary int8 values -> 4-bit floats in matrix-core fragment order (uint8 vector)."""
+    if dst is None:
+        dst = torch.empty(packed_t4_bytes(rows, K), dtype=torch.uint8, device=src.device)
+    _check(lib().pack_t4(_ptr(src), rows, K, stride_r, stride_k, _ptr(dst), _stream(stream)))
+    return dst
+
+
+def gemm_t4_mfma(M, N, K, Ap, Bp, C=None, ldc=None, stream=None):
+    """C = A B for operands packed by pack_t4 (the matrix-core counterpart of gemm_tnn / gemm_tbn / gemm_bnn)."""
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int32, device=Ap.device)
+        ldc = N
+    elif ldc is None:
+        ldc = C.stride(0)
+    _check(lib().gemm_t4_mfma(M, N, K, _ptr(Ap), _ptr(Bp), _ptr(C), ldc, _stream(stream)))
     return C
 
 

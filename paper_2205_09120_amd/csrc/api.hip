@@ -28,6 +28,7 @@ constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K m
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
 constexpr int64_t kU4MaxDepth = 74565;         // 225 * K < 2^24: fp32 sums of 4-bit products stay exact
+constexpr int64_t kT4MaxDepth = 16777215;      // K < 2^24: fp32 sums of +-1 products stay exact
 constexpr int64_t kSkinnyMax = 32;             // widest "skinny" side served by the depth-split kernel
 constexpr int kI8Instances = 10;               // kernel instances of gemm_i8_mfma selectable through lb_set_variant
 
@@ -689,6 +690,74 @@ int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const int32_t 
     const hipError_t e =
         lowbit::launch_gemm_u4(M, N, K, static_cast<const uint8_t *>(Ap), sumA, static_cast<const uint8_t *>(Bp), sumB,
                                zA, zB, C, ldc, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+size_t packed_t4_bytes(int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0 || rows > kMaxExtent || K > kT4MaxDepth)
+        return 0;
+    const int64_t RB = (rows + 31) / 32, KB = 2 * ((K + 127) / 128);
+    return (size_t)(RB * KB * 1024);
+}
+
+int pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst, void *stream)
+{
+    const char *name = "pack_t4";
+    if (rows < 0 || K < 0)
+        return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
+    if (rows == 0 || K == 0)
+        return LB_OK;
+    if (!src || !dst)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (K > kT4MaxDepth || rows > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1 rows / %lld depth positions", name,
+                    (long long)rows, (long long)K, (long long)kT4MaxDepth);
+    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
+    const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
+    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
+        return fail(LB_EINVAL,
+                    "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
+                    "stride_k=%lld rows=%lld K=%lld)",
+                    name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
+    if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
+        return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
+    if (!aligned(dst, 16))
+        return fail(LB_EINVAL, "%s: dst must be 16-byte aligned", name);
+    const hipError_t e = lowbit::launch_pack_t4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
+                                                static_cast<uint8_t *>(dst), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const void *Bp, int32_t *C, int64_t ldc, void *stream)
+{
+    const char *name = "gemm_t4_mfma";
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    // |sum| <= K < 2^24 keeps every fp32 partial sum exact
+    if (K > kT4MaxDepth)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds %lld (exact fp32 accumulation)", name, (long long)K,
+                    (long long)kT4MaxDepth);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0)
+        return LB_OK;
+    if (!Ap || !Bp || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (ldc < N)
+        return fail(LB_EINVAL, "%s: ldc=%lld < N=%lld", name, (long long)ldc, (long long)N);
+    if (ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
+    if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, 4))
+        return fail(LB_EINVAL, "%s: packed operands must be 16-byte aligned, C 4-byte aligned", name);
+    const hipError_t e = lowbit::launch_gemm_t4(M, N, K, static_cast<const uint8_t *>(Ap), static_cast<const uint8_t *>(Bp),
+                                                C, ldc, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;

@@ -13,6 +13,11 @@
 // reads it with three conflict-free ds_read_b64; fragments are ordered by row block, then depth block.  Global memory
 // therefore goes to LDS as a plain contiguous copy (global_load_lds_dwordx4), with no transposes or swizzles: like the
 // paper's reordered Ablock / Bblock buffers (Section III), the packing step writes exactly what the multiply reads.
+//
+// The same kernel also multiplies ternary / binary operands ({-1, 0, +1}: the paper's own value sets, Section III-A)
+// stored as 4-bit floats (1 sign, 2 exponent, 1 mantissa bit, bias 1: 0 and +-1 are exact), 16 bytes per lane and
+// fragment, on the same instruction at its 4-bit rate: what the matrix cores of this chip do with the operands that
+// the paper multiplies with AND / XOR / popcount (pack_t4, gemm_t4_mfma).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
@@ -28,6 +33,8 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int kFragBytes = 1536;          // 32 rows x 64 depth positions x 6 bits
 constexpr int kSegBytes = 2 * kFragBytes; // one row block x 128 depth positions: the unit a depth stage moves
 constexpr int kScaleTwo = (int)0x80808080u;  // block scale 2^(128 - 127) in every byte, whichever the opsel picks
+constexpr int kScaleOne = (int)0x7f7f7f7fu;  // block scale 1
+constexpr int kFrag4Bytes = 1024;            // 4-bit floats: 32 rows x 64 depth positions x 4 bits
 
 int g_u4_forced = -1;
 
@@ -210,6 +217,115 @@ __global__ __launch_bounds__(256) void pack_u4_strided_kernel(const uint8_t *__r
     }
 }
 
+// ---- ternary / binary values as 4-bit floats
+
+// Four int8 values in the bytes of x, taken by sign -> their four 4-bit codes (+1: 0b0010, -1: 0b1010, 0: 0) in 16 bits.
+__device__ __forceinline__ uint32_t codes4_fp4(uint32_t x)
+{
+    const uint32_t neg = x & 0x80808080u;
+    const uint32_t nz = (((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x) & 0x80808080u;  // 0x80 in every nonzero byte
+    const uint32_t c = (nz >> 6) | (neg >> 4);                                  // one code per byte (low nibble)
+    return (c & 0xfu) | ((c >> 4) & 0xf0u) | ((c >> 8) & 0xf00u) | ((c >> 12) & 0xf000u);
+}
+
+__device__ __forceinline__ uint4 encode32_fp4(const uint32_t (&w)[8])
+{
+    uint32_t f[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        f[t] = codes4_fp4(w[t]);
+    return make_uint4(f[0] | (f[1] << 16), f[2] | (f[3] << 16), f[4] | (f[5] << 16), f[6] | (f[7] << 16));
+}
+
+// Same thread mapping as pack_u4_kernel; a thread writes the 16 bytes of its slot.
+__global__ __launch_bounds__(256) void pack_t4_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                      int64_t stride, uint8_t *__restrict__ dst, int KB)
+{
+    const int tid = threadIdx.x, i = tid & 31, gg = tid >> 5;
+    const int64_t rb = blockIdx.x, r = rb * 32 + i;
+    const int G = KB * 2, units = (G + 7) / 8;
+    const bool row_ok = r < rows;
+    for (int u = blockIdx.y; u < units; u += gridDim.y) {
+        const int g = u * 8 + gg;
+        if (g >= G)
+            continue;
+        const int64_t k0 = (int64_t)g * 32;
+        uint32_t w[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            w[t] = 0u;
+        if (row_ok && k0 < K) {
+            if (k0 + 32 <= K) {
+                uint4 lo, hi;
+                const int8_t *p = src + r * stride + k0;
+                __builtin_memcpy(&lo, p, 16);
+                __builtin_memcpy(&hi, p + 16, 16);
+                w[0] = lo.x; w[1] = lo.y; w[2] = lo.z; w[3] = lo.w;
+                w[4] = hi.x; w[5] = hi.y; w[6] = hi.z; w[7] = hi.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    const int64_t k = k0 + j;
+                    uint32_t v = 0u;
+                    if (k < K)
+                        v = (uint8_t)src[r * stride + k];
+                    w[j >> 2] |= v << (8 * (j & 3));
+                }
+            }
+        }
+        uint8_t *o = dst + (rb * KB + (g >> 1)) * (int64_t)kFrag4Bytes + ((g & 1) * 32 + i) * 16;
+        *reinterpret_cast<uint4 *>(o) = encode32_fp4(w);
+    }
+}
+
+// Same thread mapping as pack_u4_strided_kernel; the four rows of a lane are four adjacent 16-byte slots.
+__global__ __launch_bounds__(256) void pack_t4_strided_kernel(const int8_t *__restrict__ src, int64_t rows, int64_t K,
+                                                              int64_t stride, uint8_t *__restrict__ dst, int KB,
+                                                              int64_t RB)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, q = lane & 31, hh = lane >> 5;
+    const int64_t r0 = (int64_t)blockIdx.x * 128 + 4 * q;
+    const int64_t rb = r0 >> 5;
+    const int G = KB * 2, units = (G + 7) / 8;
+    const bool quad_ok = r0 + 3 < rows;
+    for (int u = blockIdx.y; u < units; u += gridDim.y) {
+        const int g = u * 8 + wave * 2 + hh;
+        if (g >= G || rb >= RB)
+            continue;
+        const int64_t k0 = (int64_t)g * 32;
+        uint32_t w[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int64_t k = k0 + j;
+            uint32_t v = 0u;
+            if (k < K) {
+                const int8_t *p = src + k * stride + r0;
+                if (quad_ok) {
+                    __builtin_memcpy(&v, p, 4);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (r0 + b < rows)
+                            v |= (uint32_t)(uint8_t)p[b] << (8 * b);
+                }
+            }
+            w[j] = v;
+        }
+        uint8_t *o = dst + (rb * KB + (g >> 1)) * (int64_t)kFrag4Bytes + ((g & 1) * 32 + 4 * (q & 7)) * 16;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            uint32_t x[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const uint32_t a = __builtin_amdgcn_perm(w[4 * t + 1], w[4 * t], rr < 2 ? 0x05010400u : 0x07030602u);
+                const uint32_t b = __builtin_amdgcn_perm(w[4 * t + 3], w[4 * t + 2], rr < 2 ? 0x05010400u : 0x07030602u);
+                x[t] = __builtin_amdgcn_perm(b, a, (rr & 1) ? 0x07060302u : 0x05040100u);
+            }
+            *reinterpret_cast<uint4 *>(o + rr * 16) = encode32_fp4(x);
+        }
+    }
+}
+
 // -------------------------------------------------------------------------------------------------- product
 
 // WM x WN waves, each RM x RN MFMA blocks of 32 x 32: workgroup tile (32*RM*WM) x (32*RN*WN).  Every wave both issues
@@ -218,16 +334,24 @@ __global__ __launch_bounds__(256) void pack_u4_strided_kernel(const uint8_t *__r
 // every wave has finished reading the stage before, whose buffer the loads issued next overwrite.
 // Row blocks beyond the operand (ragged M, N) re-read the operand's last row block: always in bounds, and the
 // products they feed are never stored.
-template <int WM, int WN, int RM, int RN, int STAGES>
+// FMT is the element format of both operands as the instruction numbers them: 2 = 6-bit floats (24 bytes per lane and
+// fragment, three planes of 8, block scale 2, zero-point epilogue), 4 = 4-bit floats (16 bytes per lane, scale 1, no
+// zero points: sumA / sumB are not read).
+template <int FMT, int WM, int WN, int RM, int RN, int STAGES>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
     const uint8_t *__restrict__ Ap, const uint8_t *__restrict__ Bp, const int32_t *__restrict__ sumA,
     const int32_t *__restrict__ sumB, int M, int N, int K, int KB2, int RBA, int RBB, int32_t *__restrict__ C,
     int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
 {
+    static_assert(FMT == 2 || FMT == 4, "6-bit or 4-bit floats");
+    constexpr int kFragBytes = FMT == 2 ? 1536 : kFrag4Bytes;  // shadows the 6-bit constant of the packing kernels
+    constexpr int kSegBytes = 2 * kFragBytes;                  // one row block x 128 depth positions
+    constexpr int LPS = kSegBytes / 1024;                      // wave-wide 1 KB loads per segment
+    constexpr int kScale = FMT == 2 ? kScaleTwo : kScaleOne;
     constexpr int NW = WM * WN;
     constexpr int SA = RM * WM, SB = RN * WN;          // row-block segments of A and of B per stage
     constexpr int STAGE = (SA + SB) * kSegBytes;
-    constexpr int LOADS = (SA + SB) * 3;               // wave-wide 1 KB loads per stage
+    constexpr int LOADS = (SA + SB) * LPS;             // wave-wide 1 KB loads per stage
     constexpr int LW = LOADS / NW;                     // ... per wave
     static_assert(LOADS % NW == 0 && (STAGES - 2) * LW < 64 && STAGES >= 2, "load split / vmcnt is a 6-bit counter");
     static_assert(STAGES * STAGE <= 160 * 1024, "LDS");
@@ -246,7 +370,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
     const uint8_t *src[LW];
 #pragma unroll
     for (int t = 0; t < LW; ++t) {
-        const int q = wave * LW + t, seg = q / 3, part = q - seg * 3;
+        const int q = wave * LW + t, seg = q / LPS, part = q - seg * LPS;
         const uint8_t *base;
         if (seg < SA) {
             int rb = mb * SA + seg;
@@ -286,13 +410,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
                 acc[i][j][r] = 0.f;
 
     // Fragments of the next depth step are read while the MFMAs of the current one run (two fragment sets alternate).
-    const int a_off = (wm * RM) * kSegBytes + lane * 8;
-    const int b_off = (SA + wn * RN) * kSegBytes + lane * 8;
+    const int a_off = (wm * RM) * kSegBytes + lane * (FMT == 2 ? 8 : 16);
+    const int b_off = (SA + wn * RN) * kSegBytes + lane * (FMT == 2 ? 8 : 16);
     auto frag = [&](const uint8_t *p) __attribute__((always_inline)) {
-        const uint2 q0 = *reinterpret_cast<const uint2 *>(p);
-        const uint2 q1 = *reinterpret_cast<const uint2 *>(p + 512);
-        const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 1024);
-        return v8i{(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
+        if constexpr (FMT == 2) {
+            const uint2 q0 = *reinterpret_cast<const uint2 *>(p);
+            const uint2 q1 = *reinterpret_cast<const uint2 *>(p + 512);
+            const uint2 q2 = *reinterpret_cast<const uint2 *>(p + 1024);
+            return v8i{(int)q0.x, (int)q0.y, (int)q1.x, (int)q1.y, (int)q2.x, (int)q2.y, 0, 0};
+        } else {
+            const uint4 q = *reinterpret_cast<const uint4 *>(p);
+            return v8i{(int)q.x, (int)q.y, (int)q.z, (int)q.w, 0, 0, 0, 0};
+        }
     };
     auto read_frags = [&](int s, int ks, v8i(&a)[RM], v8i(&b)[RN]) __attribute__((always_inline)) {
         const uint8_t *st = smem + (s % STAGES) * STAGE + ks * kFragBytes;
@@ -308,8 +437,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
         for (int i = i0; i < i1; ++i)
 #pragma unroll
             for (int j = 0; j < RN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], 2, 2, 0, kScaleTwo, 0,
-                                                                             kScaleTwo);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i], b[j], acc[i][j], FMT, FMT, 0, kScale, 0,
+                                                                             kScale);
     };
     // "stage s holds its data and the stage before it is free": own loads landed (all but `in_flight` newer ones),
     // then the workgroup barrier
@@ -374,8 +503,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
                         if (t < LW)
                             issue_one(s + STAGES, t);
                     }
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[1][i], fb[1][j], acc[i][j], 2, 2, 0,
-                                                                                 kScaleTwo, 0, kScaleTwo);
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[1][i], fb[1][j], acc[i][j], FMT, FMT, 0,
+                                                                                 kScale, 0, kScale);
                     __builtin_amdgcn_sched_barrier(0);
                 }
         } else {
@@ -402,6 +531,21 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
     // The row sums of all the rows a lane stores to are fetched up front, from indices clamped into range, so that
     // the loads go out together instead of one in front of every guarded store.
     const int m0 = mb * 32 * SA, n0 = nb * 32 * SB;
+    if constexpr (FMT == 4) {
+#pragma unroll
+        for (int j = 0; j < RN; ++j) {
+            const int col = n0 + (wn * RN + j) * 32 + (lane & 31);
+#pragma unroll
+            for (int i = 0; i < RM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + (wm * RM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (col < N && row < M)
+                        C[(int64_t)row * ldc + col] = (int)acc[i][j][r];
+                }
+        }
+        return;
+    }
     const int kzz = K * zA * zB;
     int rcorr[RM][16];
 #pragma unroll
@@ -427,7 +571,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
     }
 }
 
-template <int WM, int WN, int RM, int RN, int STAGES>
+template <int FMT, int WM, int WN, int RM, int RN, int STAGES>
 hipError_t launch_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
                      const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
 {
@@ -437,7 +581,7 @@ hipError_t launch_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const i
     const int64_t tiles_per_xcd = (tiles + 7) / 8;
     if (tiles_per_xcd * 8 > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_u4_fp6_kernel<WM, WN, RM, RN, STAGES>), dim3((unsigned)(tiles_per_xcd * 8)),
+    hipLaunchKernelGGL((gemm_u4_fp6_kernel<FMT, WM, WN, RM, RN, STAGES>), dim3((unsigned)(tiles_per_xcd * 8)),
                        dim3(64 * WM * WN), 0, stream, Ap, Bp, sumA, sumB, (int)M, (int)N, (int)K,
                        (int)((K + 127) / 128), (int)((M + 31) / 32), (int)((N + 31) / 32), C, ldc, (int)nMB, (int)nNB,
                        (int)tiles_per_xcd, zA, zB);
@@ -485,10 +629,50 @@ hipError_t launch_gemm_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, co
         inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
     }
     switch (inst) {
-    case 0: return launch_u4<2, 2, 4, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    case 1: return launch_u4<4, 2, 2, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    case 2: return launch_u4<2, 2, 2, 2, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    default: return launch_u4<2, 2, 1, 1, 4>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 0: return launch_u4<2, 2, 2, 4, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 1: return launch_u4<2, 4, 2, 2, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 2: return launch_u4<2, 2, 2, 2, 2, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    default: return launch_u4<2, 2, 2, 1, 1, 4>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    }
+}
+
+hipError_t launch_pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint8_t *dst,
+                          hipStream_t stream)
+{
+    const int64_t RB = (rows + 31) / 32;
+    const int KB = 2 * (int)((K + 127) / 128);
+    if (RB > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    const int units = (KB * 2 + 7) / 8;
+    if (stride_k == 1) {
+        int64_t chunks = (4096 + RB - 1) / RB;
+        chunks = chunks < 1 ? 1 : chunks > units ? units : chunks;
+        hipLaunchKernelGGL(pack_t4_kernel, dim3((unsigned)RB, (unsigned)chunks), dim3(256), 0, stream, src, rows, K,
+                           stride_r, dst, KB);
+    } else {
+        const int64_t RB4 = (rows + 127) / 128;
+        int64_t ch = (4096 + RB4 - 1) / RB4;
+        ch = ch < 1 ? 1 : ch > units ? units : ch;
+        hipLaunchKernelGGL(pack_t4_strided_kernel, dim3((unsigned)RB4, (unsigned)ch), dim3(256), 0, stream, src, rows, K,
+                           stride_k, dst, KB, RB);
+    }
+    return hipGetLastError();
+}
+
+// Same instances as launch_gemm_u4; the 4-bit stage of a 256 x 256 tile is 32 KB, so its ring holds four of them.
+hipError_t launch_gemm_t4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const uint8_t *Bp, int32_t *C, int64_t ldc,
+                          hipStream_t stream)
+{
+    int inst = g_u4_forced;
+    if (inst < 0) {
+        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+        inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
+    }
+    switch (inst) {
+    case 0: return launch_u4<4, 2, 2, 4, 4, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
+    case 1: return launch_u4<4, 4, 2, 2, 4, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
+    case 2: return launch_u4<4, 2, 2, 2, 2, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
+    default: return launch_u4<4, 2, 2, 1, 1, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
     }
 }
 

@@ -127,6 +127,11 @@ hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t s
                           uint8_t *dst, int32_t *sums, hipStream_t stream);
 hipError_t launch_gemm_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
                           const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream);
+// The same kernel on ternary / binary operands stored as 4-bit floats (no sums, no zero points).
+hipError_t launch_pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint8_t *dst,
+                          hipStream_t stream);
+hipError_t launch_gemm_t4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const uint8_t *Bp, int32_t *C, int64_t ldc,
+                          hipStream_t stream);
 int u4_num_instances();
 void u4_force_instance(int t);  // -1 = shape-based
 

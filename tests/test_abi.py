@@ -145,6 +145,25 @@ def test_u4_argument_validation(L):
     assert g(0, 4, 64, None, None, None, None, 0, 0, None, 4, None) == binding.LB_OK
 
 
+def test_t4_argument_validation(L):
+    fake = 0x1000
+    assert L.packed_t4_bytes(1, 1) == 2 * 1024 and L.packed_t4_bytes(1024, 4608) == 32 * 72 * 1024
+    assert L.packed_t4_bytes(0, 5) == 0
+    p = L.pack_t4
+    assert p(None, 4, 64, 64, 1, fake, None) == binding.LB_EINVAL
+    assert p(fake, 4, 64, 32, 1, fake, None) == binding.LB_EINVAL                            # stride_r < K
+    assert p(fake, 4, 64, 64, 1, fake + 8, None) == binding.LB_EINVAL                        # dst misaligned
+    assert p(fake, 4, 1 << 24, 1 << 24, 1, fake, None) == binding.LB_EOVERFLOW
+    assert p(None, 0, 64, 64, 1, None, None) == binding.LB_OK
+    g = L.gemm_t4_mfma
+    assert g(4, 4, 0, fake, fake, fake, 4, None) == binding.LB_EINVAL
+    assert g(4, 4, 1 << 24, fake, fake, fake, 4, None) == binding.LB_EOVERFLOW
+    assert g(4, 4, 64, fake, None, fake, 4, None) == binding.LB_EINVAL
+    assert g(4, 4, 64, fake, fake, fake, 3, None) == binding.LB_EINVAL                       # ldc < N
+    assert g(4, 4, 64, fake + 4, fake, fake, 4, None) == binding.LB_EINVAL                   # Ap misaligned
+    assert g(0, 4, 64, None, None, None, 4, None) == binding.LB_OK
+
+
 def test_requant_argument_validation(L):
     fake = 0x1000
     f = L.gemm_requant
