@@ -356,6 +356,22 @@ def main() -> int:
                                 "frac_of_fp6_mfma_peak": w.ops / tu4 / 10.1e15,
                                 "speedup_vs_int8_mfma": ti8 / tu4, "gemm_tnn_speed_relative": tu4 / gemm_s}
         del uA, uB, uAp, usA, uBp, usB
+        # the same ternary operands as 4-bit floats on the matrix cores (not the paper's method: what this chip's
+        # low-precision matrix instruction does with them); step = pack A + pack B + product, like `value`
+        tAp, tBp = lb.pack_t4(dA, M, K, K, 1), lb.pack_t4(dB, N, K, 1, N)
+
+        def t4_step():
+            lb.pack_t4(dA, M, K, K, 1, tAp)
+            lb.pack_t4(dB, N, K, 1, N, tBp)
+            lb.gemm_t4_mfma(M, N, K, tAp, tBp, C, N)
+
+        tt4 = dev_time(lambda: lb.gemm_t4_mfma(M, N, K, tAp, tBp, C, N), 20)
+        tt4s = dev_time(t4_step, 10)
+        extra["fp4_mfma_same_operands"] = {"gemm_tops": w.ops / tt4 / 1e12, "gemm_ms": tt4 * 1e3,
+                                           "step_incl_packing_tops": w.ops / tt4s / 1e12, "step_ms": tt4s * 1e3,
+                                           "frac_of_fp4_mfma_peak": w.ops / tt4 / 10.1e15,
+                                           "speedup_vs_gemm_tnn": gemm_s / tt4, "speedup_vs_int8_mfma": ti8 / tt4}
+        del tAp, tBp
         # context only: the vendor library's int8 GEMM (hipBLASLt behind torch._int_mm) on the same matrices
         try:
             torch._int_mm(dA, dB)
