@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblowbit_gemm.so")
-SOURCES = ["api.hip", "pack.hip", "gemm_popc.hip", "gemm_skinny.hip", "gemm_i8_mfma.hip", "gemm_i8_skinny.hip", "gemm_u4_fp6.hip", "im2col.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "pack.hip", "gemm_popc.hip", "gemm_skinny.hip", "gemm_i8_mfma.hip", "gemm_i8_skinny.hip", "gemm_mx_mfma.hip", "im2col.hip", "calibrate.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     # keep the compiler from forming packed-FP32 instructions

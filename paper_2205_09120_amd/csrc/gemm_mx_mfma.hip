@@ -2,7 +2,7 @@
 // algorithm (Table II, Section IV; the quantized product and its zero-point expansion are eq. (2) and (3)).
 //
 // gfx950 has no 4-bit integer matrix instruction, but its scaled MFMA takes 6-bit floats (1 sign, 2 exponent, 3 mantissa
-// bits, bias 1) at twice the 8-bit rate, and with a block scale of 2 that type represents every integer 0..15 exactly
+// bits, bias 1) at a higher rate than 8-bit operands (published: twice; measured here: 1.6 times), and with a block scale of 2 that type represents every integer 0..15 exactly
 // (0, 0.5, ..., 7.5 doubled).  Products of such values and their fp32 sums are exact while the sum stays below 2^24,
 // i.e. for K <= 74565 (15 * 15 * K < 2^24): the result is the integer product, bit for bit.
 //
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(256) void pack_t4_strided_kernel(const int8_t *__re
 // fragment, three planes of 8, block scale 2, zero-point epilogue), 4 = 4-bit floats (16 bytes per lane, scale 1, no
 // zero points: sumA / sumB are not read).
 template <int FMT, int WM, int WN, int RM, int RN, int STAGES>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_u4_fp6_kernel(
+__global__ __launch_bounds__(64 * WM * WN) void gemm_mx_kernel(
     const uint8_t *__restrict__ Ap, const uint8_t *__restrict__ Bp, const int32_t *__restrict__ sumA,
     const int32_t *__restrict__ sumB, int M, int N, int K, int KB2, int RBA, int RBB, int32_t *__restrict__ C,
     int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
@@ -581,7 +581,7 @@ hipError_t launch_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const i
     const int64_t tiles_per_xcd = (tiles + 7) / 8;
     if (tiles_per_xcd * 8 > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((gemm_u4_fp6_kernel<FMT, WM, WN, RM, RN, STAGES>), dim3((unsigned)(tiles_per_xcd * 8)),
+    hipLaunchKernelGGL((gemm_mx_kernel<FMT, WM, WN, RM, RN, STAGES>), dim3((unsigned)(tiles_per_xcd * 8)),
                        dim3(64 * WM * WN), 0, stream, Ap, Bp, sumA, sumB, (int)M, (int)N, (int)K,
                        (int)((K + 127) / 128), (int)((M + 31) / 32), (int)((N + 31) / 32), C, ldc, (int)nMB, (int)nNB,
                        (int)tiles_per_xcd, zA, zB);

@@ -121,7 +121,7 @@ void i8_force_tile(int t);  // -1 = shape-based, 0 = 128x128, 1 = 256x256, 2 = 2
                             // 256x128 / 128x128 / 64x64 with 3 stages of 128 depth bytes (4 of 64 if the depth is
                             // not a multiple of 128); ragged extents allowed
 
-// 4-bit unsigned operands as 6-bit floats on the scaled matrix-core instruction (gemm_u4_fp6.hip).  Packed operands
+// 4-bit unsigned operands as 6-bit floats on the scaled matrix-core instruction (gemm_mx_mfma.hip).  Packed operands
 // are fragment-major (see that file); sums holds one int32 per row.  Element (r,k) = src[r*stride_r + k*stride_k].
 hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
                           uint8_t *dst, int32_t *sums, hipStream_t stream);
