@@ -34,6 +34,7 @@ constexpr int kFragBytes = 1536;          // 32 rows x 64 depth positions x 6 bi
 constexpr int kSegBytes = 2 * kFragBytes; // one row block x 128 depth positions: the unit a depth stage moves
 constexpr int kScaleTwo = (int)0x80808080u;  // block scale 2^(128 - 127) in every byte, whichever the opsel picks
 constexpr int kScaleOne = (int)0x7f7f7f7fu;  // block scale 1
+constexpr int kComputeUnits = 256;           // MI355X
 constexpr int kFrag4Bytes = 1024;            // 4-bit floats: 32 rows x 64 depth positions x 4 bits
 
 int g_u4_forced = -1;
@@ -588,6 +589,54 @@ hipError_t launch_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const i
     return hipGetLastError();
 }
 
+// Instances: 0 = 256 x 256 tile (4 waves of 128 x 128), 1 = 256 x 256 (8 waves of 64 x 128), 2 = 128 x 128 (4 waves of
+// 64 x 64), 3 = 64 x 64 (4 waves of 32 x 32).  Ring depth: 3, 3, 3, 4 stages for 6-bit floats, 4 for 4-bit floats.
+template <int FMT>
+hipError_t launch_mx_instance(int inst, int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA,
+                              const uint8_t *Bp, const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc,
+                              hipStream_t stream)
+{
+    constexpr int S = FMT == 2 ? 3 : 4;
+    switch (inst) {
+    case 0: return launch_u4<FMT, 2, 2, 4, 4, S>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 1: return launch_u4<FMT, 4, 2, 2, 4, S>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    case 2: return launch_u4<FMT, 2, 2, 2, 2, S>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    default: return launch_u4<FMT, 2, 2, 1, 1, 4>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    }
+}
+
+// Shape-based choice.  256 x 256 tiles run one workgroup per compute unit, in rounds of 256 tiles; when the last round
+// would be at most half full (784 tiles: 16 of them would run alone for a whole tile time), the columns of C that
+// the full rounds cover go to one launch and the remaining columns to a second launch with 64 x 64 (or 128 x 128)
+// tiles, which spreads them over the whole machine.  The packed right operand is ordered by row block, so a column
+// range of C is a contiguous piece of it.
+template <int FMT>
+hipError_t launch_mx_auto(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
+                          const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
+{
+    if (g_u4_forced >= 0)
+        return launch_mx_instance<FMT>(g_u4_forced, M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    const int64_t nMB = (M + 255) / 256, nNB = (N + 255) / 256;
+    const int64_t t256 = nMB * nNB, t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const int inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
+    const int64_t rest = t256 % kComputeUnits;
+    if (inst == 1 && t256 > kComputeUnits && rest > 0 && rest <= kComputeUnits / 2) {
+        const int64_t c1 = (t256 - rest) / nMB;  // whole columns of tiles inside the full rounds
+        if (c1 >= 1 && c1 < nNB) {
+            const int64_t N1 = c1 * 256, Nt = N - N1;
+            const hipError_t e = launch_mx_instance<FMT>(1, M, N1, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+            if (e != hipSuccess)
+                return e;
+            constexpr int64_t kSeg = FMT == 2 ? 3072 : 2048;
+            const int64_t t64 = ((M + 63) / 64) * ((Nt + 63) / 64);
+            return launch_mx_instance<FMT>(t64 <= 4 * kComputeUnits ? 3 : 2, M, Nt, K, Ap, sumA,
+                                           Bp + (N1 / 32) * ((K + 127) / 128) * kSeg, sumB ? sumB + N1 : nullptr, zA, zB,
+                                           C + N1, ldc, stream);
+        }
+    }
+    return launch_mx_instance<FMT>(inst, M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+}
+
 }  // namespace
 
 int u4_num_instances() { return 4; }
@@ -618,22 +667,16 @@ hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t s
     return hipGetLastError();
 }
 
-// Instances: 0 = 256 x 256 tile (4 waves of 128 x 128), 1 = 256 x 256 (8 waves of 64 x 128), 2 = 128 x 128 (4 waves of
-// 64 x 64), 3 = 64 x 64 (4 waves of 32 x 32, 4 stages).
 hipError_t launch_gemm_u4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
                           const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    int inst = g_u4_forced;
-    if (inst < 0) {
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
-        inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
-    }
-    switch (inst) {
-    case 0: return launch_u4<2, 2, 2, 4, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    case 1: return launch_u4<2, 4, 2, 2, 4, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    case 2: return launch_u4<2, 2, 2, 2, 2, 3>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    default: return launch_u4<2, 2, 2, 1, 1, 4>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
-    }
+    return launch_mx_auto<2>(M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+}
+
+hipError_t launch_gemm_t4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const uint8_t *Bp, int32_t *C, int64_t ldc,
+                          hipStream_t stream)
+{
+    return launch_mx_auto<4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
 }
 
 hipError_t launch_pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, uint8_t *dst,
@@ -657,23 +700,6 @@ hipError_t launch_pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t st
                            stride_k, dst, KB, RB);
     }
     return hipGetLastError();
-}
-
-// Same instances as launch_gemm_u4; the 4-bit stage of a 256 x 256 tile is 32 KB, so its ring holds four of them.
-hipError_t launch_gemm_t4(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const uint8_t *Bp, int32_t *C, int64_t ldc,
-                          hipStream_t stream)
-{
-    int inst = g_u4_forced;
-    if (inst < 0) {
-        const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256), t128 = ((M + 127) / 128) * ((N + 127) / 128);
-        inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
-    }
-    switch (inst) {
-    case 0: return launch_u4<4, 2, 2, 4, 4, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
-    case 1: return launch_u4<4, 4, 2, 2, 4, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
-    case 2: return launch_u4<4, 2, 2, 2, 2, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
-    default: return launch_u4<4, 2, 2, 1, 1, 4>(M, N, K, Ap, nullptr, Bp, nullptr, 0, 0, C, ldc, stream);
-    }
 }
 
 }  // namespace lowbit

@@ -44,8 +44,9 @@ def test_pack_t4_takes_values_by_sign_and_honours_leading_dimensions():
     assert np.array_equal(got.cpu().numpy(), want)
 
 
+# the last one has a partial last round of 256 x 256 tiles (289 tiles): two launches, the second with small tiles
 SHAPES = [(1, 1, 1), (3, 5, 7), (64, 64, 128), (65, 33, 129), (100, 260, 300), (256, 256, 512), (300, 520, 1000),
-          (513, 130, 4608)]
+          (513, 130, 4608), (4100, 4300, 2100)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
