@@ -243,7 +243,8 @@ LB_API int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64
  *             sums  device, int32[rows]: sum of the K values of each row (overwritten)
  *             Enqueues two kernels on `stream`.  rows == 0 or K == 0: nothing is written.
  *   gemm_u4_mfma    Ap / sumA from pack_u4 of A (M strings), Bp / sumB from pack_u4 of B (N strings), same K;
- *                   C device, int32 row-major M x N, ldc >= N, overwritten.
+ *                   C device, int32 row-major M x N, ldc >= N, overwritten.  May enqueue two kernels (column ranges
+ *                   of C with different tile sizes).
  * Errors as for the other entry points (LB_EINVAL for null / misaligned pointers, bad strides, zero points outside
  * 0..15, K < 1; LB_EOVERFLOW for K > 74565 or extents beyond 2^31 - 1).
  */
@@ -266,7 +267,8 @@ LB_API int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const i
  *                       (rb * 2*ceil(K/128) + kb) * 1024; inside it 64 slots of 16 bytes, slot 32*h + i = depth positions
  *                       64*kb + 32*h .. + 31 of row 32*rb + i, position j in bits 4j .. 4j+3 (little-endian)
  *   gemm_t4_mfma  Ap from pack_t4 of A (M strings), Bp from pack_t4 of B (N strings), same K; C device, int32
- *                 row-major M x N, ldc >= N, overwritten.
+ *                 row-major M x N, ldc >= N, overwritten.  May enqueue two kernels (column ranges of C with different
+ *                 tile sizes).
  * Errors as for the other entry points.
  */
 LB_API size_t packed_t4_bytes(int64_t rows, int64_t K);
