@@ -246,7 +246,8 @@ LB_API int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64
  *                   C device, int32 row-major M x N, ldc >= N, overwritten.  May enqueue two kernels (column ranges
  *                   of C with different tile sizes).
  * Errors as for the other entry points (LB_EINVAL for null / misaligned pointers, bad strides, zero points outside
- * 0..15, K < 1; LB_EOVERFLOW for K > 74565 or extents beyond 2^31 - 1).
+ * 0..15, K < 1; LB_EOVERFLOW for K > 74565, for rows beyond 2^31 - 1 in pack_u4 and for M or N beyond 2^31 - 256 in
+ * gemm_u4_mfma).
  */
 LB_API size_t packed_u4_bytes(int64_t rows, int64_t K);
 LB_API int pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst,
@@ -269,7 +270,7 @@ LB_API int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const i
  *   gemm_t4_mfma  Ap from pack_t4 of A (M strings), Bp from pack_t4 of B (N strings), same K; C device, int32
  *                 row-major M x N, ldc >= N, overwritten.  May enqueue two kernels (column ranges of C with different
  *                 tile sizes).
- * Errors as for the other entry points.
+ * Errors as for the other entry points; LB_EOVERFLOW for K >= 2^24 and for M or N beyond 2^31 - 256.
  */
 LB_API size_t packed_t4_bytes(int64_t rows, int64_t K);
 LB_API int pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst,

@@ -28,6 +28,7 @@ constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K m
 constexpr int64_t kMaxExtent = 0x7fffffffLL;   // kernels index bit strings with 32-bit integers
 
 constexpr int64_t kU4MaxDepth = 74565;         // 225 * K < 2^24: fp32 sums of 4-bit products stay exact
+constexpr int64_t kMxMaxExtent = 0x7fffff00LL;  // matrix-core kernels: row / column indices of a 256-wide tile stay in int32
 constexpr int64_t kT4MaxDepth = 16777215;      // K < 2^24: fp32 sums of +-1 products stay exact
 constexpr int64_t kSkinnyMax = 32;             // widest "skinny" side served by the depth-split kernel
 constexpr int kI8Instances = 10;               // kernel instances of gemm_i8_mfma selectable through lb_set_variant
@@ -675,8 +676,8 @@ int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const int32_t 
     if (K > kU4MaxDepth)
         return fail(LB_EOVERFLOW, "%s: K=%lld exceeds %lld (exact fp32 accumulation of 4-bit products)", name,
                     (long long)K, (long long)kU4MaxDepth);
-    if (M > kMaxExtent || N > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M > kMxMaxExtent || N > kMxMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-256", name, (long long)M, (long long)N);
     if (M == 0 || N == 0)
         return LB_OK;
     if (!Ap || !Bp || !sumA || !sumB || !C)
@@ -744,8 +745,8 @@ int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const void *Bp
     if (K > kT4MaxDepth)
         return fail(LB_EOVERFLOW, "%s: K=%lld exceeds %lld (exact fp32 accumulation)", name, (long long)K,
                     (long long)kT4MaxDepth);
-    if (M > kMaxExtent || N > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M > kMxMaxExtent || N > kMxMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-256", name, (long long)M, (long long)N);
     if (M == 0 || N == 0)
         return LB_OK;
     if (!Ap || !Bp || !C)

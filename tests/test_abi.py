@@ -139,6 +139,7 @@ def test_u4_argument_validation(L):
     assert g(4, 4, 0, fake, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL
     assert g(4, 4, 74566, fake, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EOVERFLOW
     assert b"74565" in L.lb_last_error()
+    assert g(4, (1 << 31) - 255, 64, fake, fake, fake, fake, 0, 0, fake, 1 << 31, None) == binding.LB_EOVERFLOW
     assert g(4, 4, 64, fake, None, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL     # null sums
     assert g(4, 4, 64, fake, fake, fake, fake, 0, 0, fake, 3, None) == binding.LB_EINVAL     # ldc < N
     assert g(4, 4, 64, fake + 4, fake, fake, fake, 0, 0, fake, 4, None) == binding.LB_EINVAL  # Ap misaligned
@@ -160,6 +161,7 @@ def test_t4_argument_validation(L):
     assert g(4, 4, 1 << 24, fake, fake, fake, 4, None) == binding.LB_EOVERFLOW
     assert g(4, 4, 64, fake, None, fake, 4, None) == binding.LB_EINVAL
     assert g(4, 4, 64, fake, fake, fake, 3, None) == binding.LB_EINVAL                       # ldc < N
+    assert g((1 << 31) - 255, 4, 64, fake, fake, fake, 4, None) == binding.LB_EOVERFLOW      # tile indices past int32
     assert g(4, 4, 64, fake + 4, fake, fake, 4, None) == binding.LB_EINVAL                   # Ap misaligned
     assert g(0, 4, 64, None, None, None, 4, None) == binding.LB_OK
 
