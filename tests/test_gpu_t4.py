@@ -137,3 +137,38 @@ def test_t4_random_sweep():
             assert (got[:, N:] == 99).all(), n
     finally:
         lb.lb_set_variant(5, -1)
+
+
+def test_t4_captured_in_a_graph_replays_exactly():
+    """pack_t4 + gemm_t4_mfma on a shape whose product is two launches (289 tiles of 256 x 256: the last columns go to a
+    second launch), captured once and replayed with new inputs and eager work in between."""
+    M, N, K = 4100, 4300, 300
+    dA = torch.zeros((M, K), dtype=torch.int8, device="cuda")
+    dB = torch.zeros((K, N), dtype=torch.int8, device="cuda")
+    Ap = torch.empty(lb.packed_t4_bytes(M, K), dtype=torch.uint8, device="cuda")
+    Bp = torch.empty(lb.packed_t4_bytes(N, K), dtype=torch.uint8, device="cuda")
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+
+    def pipeline():
+        lb.pack_t4(dA, M, K, K, 1, Ap)
+        lb.pack_t4(dB, N, K, 1, N, Bp)
+        lb.gemm_t4_mfma(M, N, K, Ap, Bp, C, N)
+
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        pipeline()
+    torch.cuda.current_stream().wait_stream(st)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        pipeline()
+    for rep in range(3):
+        A, B = synth.make_custom("tnn", M, N, K, seed=700 + rep)
+        dA.copy_(torch.from_numpy(A))
+        dB.copy_(torch.from_numpy(B))
+        C.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), oracle.gemm(A, B)), rep
