@@ -169,3 +169,34 @@ def test_im2col_packed_more_than_2_pow_31_pieces():
         want = bitref.pack_binary(np.ascontiguousarray(col.T)).reshape(-1)
         assert np.array_equal(row, want), int(n)
     del Bp
+
+
+def test_matrix_core_products_more_than_2_pow_31_outputs():
+    """gemm_t4_mfma and gemm_u4_mfma on 46500 x 46400 outputs: sampled entries against the oracle, every entry of the
+    4-bit float product against gemm_bnn's output (itself checked above), and the range every entry must lie in."""
+    M, N, K = 46500, 46400, 100
+    say(f"gemm_t4_mfma / gemm_u4_mfma M={M} N={N} K={K}: {M * N} outputs")
+    A, B = synth.make_custom("bnn", M, N, K, seed=31)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    ii, jj = sample_indices(M, N, 50000, seed=33)
+    di, dj = torch.from_numpy(ii).cuda(), torch.from_numpy(jj).cuda()
+    want = oracle.gemm_samples(A, B, ii, jj)
+    C = torch.full((M, N), -777, dtype=torch.int32, device="cuda")
+    lb.gemm_t4_mfma(M, N, K, lb.pack_t4(dA, M, K, K, 1), lb.pack_t4(dB, N, K, 1, N), C, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(C[di, dj].cpu().numpy(), want)
+    assert int(C.abs().max()) <= K and int((C & 1).sum()) == 0          # K even: every binary product is even
+    C2 = torch.empty_like(C)
+    lb.gemm("bnn", M, N, K, lb.pack_a("bnn", dA), lb.pack_b("bnn", dB), C2, N)
+    torch.cuda.synchronize()
+    assert torch.equal(C, C2)
+    del C2
+    # 4-bit unsigned: values {0, 2} with zero point 1 are the same +-1 matrices
+    uA, uB = (dA + 1).to(torch.uint8), (dB + 1).to(torch.uint8)
+    Ap, sA = lb.pack_u4(uA, M, K, K, 1)
+    Bp, sB = lb.pack_u4(uB, N, K, 1, N)
+    C.fill_(-777)
+    lb.gemm_u4_mfma(M, N, K, Ap, sA, Bp, sB, 1, 1, C, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(C[di, dj].cpu().numpy(), want)
+    assert int(C.abs().max()) <= K and int((C & 1).sum()) == 0
