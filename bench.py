@@ -398,6 +398,10 @@ def main() -> int:
                 tlib = graph_time(lambda: torch._int_mm(da, db, out=c_), 20, 20)
             except Exception:
                 tlib = None
+            # the same operands as 4-bit floats on the matrix cores (second comparison point)
+            ta_, tb_ = lb.pack_t4(da, ww.M, ww.K, ww.K, 1), lb.pack_t4(db, ww.N, ww.K, 1, ww.N)
+            t4 = graph_time(lambda: lb.gemm_t4_mfma(ww.M, ww.N, ww.K, ta_, tb_, c_, ww.N), 20, 20)
+            del ta_, tb_
             packed_bytes = (ap_.numel() + bp_.numel()) * 8 + c_.numel() * 4
             cold = None
             if name.startswith("cfg5_"):
@@ -416,6 +420,7 @@ def main() -> int:
                             "speedup_vs_int8_mfma": t8 / t,
                             "library_int8_us": None if tlib is None else tlib * 1e6,
                             "speedup_vs_faster_int8_kernel": (t8 if tlib is None else min(t8, tlib)) / t,
+                            "fp4_mfma_us": t4 * 1e6, "speedup_vs_fp4_mfma": t4 / t,
                             "valu_frac": ww.M * ww.N * (ww.K / 32.0) * LANE_INSTR[ww.kind] / t / 1e12 / VALU_PEAK_TOPS,
                             "hbm_frac": packed_bytes / t / 1e9 / HBM_PEAK_GBS}
             if cold is not None:
