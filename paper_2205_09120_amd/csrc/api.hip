@@ -48,31 +48,47 @@ size_t packed_bytes(int64_t rows, int64_t K, int64_t unit)
     return (size_t)(rows * KW * unit);
 }
 
-int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r,
-            int64_t stride_k, uint64_t *dst, void *stream)
+// Argument rules shared by every packing entry point.  *nothing is set when rows == 0 or K == 0 (valid, nothing to do);
+// *k_contig tells which of the two accepted source layouts was given.
+int check_pack(const char *name, const void *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
+               const void *dst, int64_t max_depth, bool *nothing, bool *k_contig)
 {
+    *nothing = false;
     if (rows < 0 || K < 0)
         return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
-    if (rows == 0 || K == 0)
+    if (rows == 0 || K == 0) {
+        *nothing = true;
         return LB_OK;
+    }
     if (!src || !dst)
         return fail(LB_EINVAL, "%s: null pointer", name);
-    if (K > kMaxDepth || rows > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1", name, (long long)rows, (long long)K);
+    if (K > max_depth || rows > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1 rows / %lld depth positions", name,
+                    (long long)rows, (long long)K, (long long)max_depth);
     // a single bit string (rows == 1) or a single depth position (K == 1) makes the other stride irrelevant
-    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
+    *k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
     const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
-    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
+    if (stride_r < 1 || stride_k < 1 || !(*k_contig || k_strided))
         return fail(LB_EINVAL,
                     "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
                     "stride_k=%lld rows=%lld K=%lld)",
                     name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
     if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
         return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
-    if (packed_bytes(rows, K, ternary ? 16 : 8) == 0)
-        return fail(LB_EOVERFLOW, "%s: packed size overflows", name);
     if (!aligned(dst, 16))
         return fail(LB_EINVAL, "%s: dst must be 16-byte aligned", name);
+    return LB_OK;
+}
+
+int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int64_t K, int64_t stride_r,
+            int64_t stride_k, uint64_t *dst, void *stream)
+{
+    bool nothing, k_contig;
+    const int rc = check_pack(name, src, rows, K, stride_r, stride_k, dst, kMaxDepth, &nothing, &k_contig);
+    if (rc != LB_OK || nothing)
+        return rc;
+    if (packed_bytes(rows, K, ternary ? 16 : 8) == 0)
+        return fail(LB_EOVERFLOW, "%s: packed size overflows", name);
     const hipError_t e =
         lowbit::launch_pack(ternary, src, rows, K, stride_r, stride_k, dst, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -635,26 +651,12 @@ int pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64
             void *stream)
 {
     const char *name = "pack_u4";
-    if (rows < 0 || K < 0)
-        return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
-    if (rows == 0 || K == 0)
-        return LB_OK;
-    if (!src || !dst || !sums)
-        return fail(LB_EINVAL, "%s: null pointer", name);
-    if (K > kU4MaxDepth || rows > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1 rows / %lld depth positions", name,
-                    (long long)rows, (long long)K, (long long)kU4MaxDepth);
-    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
-    const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
-    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
-        return fail(LB_EINVAL,
-                    "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
-                    "stride_k=%lld rows=%lld K=%lld)",
-                    name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
-    if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
-        return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
-    if (!aligned(dst, 16) || !aligned(sums, 4))
-        return fail(LB_EINVAL, "%s: dst must be 16-byte aligned, sums 4-byte aligned", name);
+    bool nothing, k_contig;
+    const int rc = check_pack(name, src, rows, K, stride_r, stride_k, dst, kU4MaxDepth, &nothing, &k_contig);
+    if (rc != LB_OK || nothing)
+        return rc;
+    if (!sums || !aligned(sums, 4))
+        return fail(LB_EINVAL, "%s: sums must be a 4-byte aligned device pointer", name);
     const hipError_t e = lowbit::launch_pack_u4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
                                                 static_cast<uint8_t *>(dst), sums, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -707,26 +709,10 @@ size_t packed_t4_bytes(int64_t rows, int64_t K)
 int pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k, void *dst, void *stream)
 {
     const char *name = "pack_t4";
-    if (rows < 0 || K < 0)
-        return fail(LB_EINVAL, "%s: rows=%lld K=%lld must be >= 0", name, (long long)rows, (long long)K);
-    if (rows == 0 || K == 0)
-        return LB_OK;
-    if (!src || !dst)
-        return fail(LB_EINVAL, "%s: null pointer", name);
-    if (K > kT4MaxDepth || rows > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: rows=%lld K=%lld exceed 2^31-1 rows / %lld depth positions", name,
-                    (long long)rows, (long long)K, (long long)kT4MaxDepth);
-    const bool k_contig = stride_k == 1 && (rows == 1 || stride_r >= K);
-    const bool k_strided = stride_r == 1 && (K == 1 || stride_k >= rows);
-    if (stride_r < 1 || stride_k < 1 || !(k_contig || k_strided))
-        return fail(LB_EINVAL,
-                    "%s: need stride_k=1 with stride_r>=K, or stride_r=1 with stride_k>=rows (got stride_r=%lld "
-                    "stride_k=%lld rows=%lld K=%lld)",
-                    name, (long long)stride_r, (long long)stride_k, (long long)rows, (long long)K);
-    if (stride_r > INT64_MAX / rows || stride_k > INT64_MAX / K)
-        return fail(LB_EOVERFLOW, "%s: source extent overflows", name);
-    if (!aligned(dst, 16))
-        return fail(LB_EINVAL, "%s: dst must be 16-byte aligned", name);
+    bool nothing, k_contig;
+    const int rc = check_pack(name, src, rows, K, stride_r, stride_k, dst, kT4MaxDepth, &nothing, &k_contig);
+    if (rc != LB_OK || nothing)
+        return rc;
     const hipError_t e = lowbit::launch_pack_t4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
                                                 static_cast<uint8_t *>(dst), static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
