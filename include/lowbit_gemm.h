@@ -64,6 +64,11 @@ LB_API const char *lb_last_error(void);
 /* LB_FORMAT_VERSION the library was built with. */
 LB_API int lb_format_version(void);
 
+/* 1 if a device with this architecture name (hipDeviceProp_t::gcnArchName, e.g. "gfx950:sramecc+:xnack-") can run
+ * the library, else 0.  The library holds gfx950 machine code only; on any other device every entry point that would
+ * launch a kernel returns LB_EUNSUPPORTED instead (checked once per device).  Host logic, usable without a GPU. */
+LB_API int lb_arch_supported(const char *gcn_arch_name);
+
 /* Bytes of a packed operand of `rows` bit strings of depth K: rows*ceil(K/64)*8 (binary) or *16 (ternary).
  * Returns 0 when rows < 0, K < 0 or the size overflows size_t. */
 LB_API size_t packed_binary_bytes(int64_t rows, int64_t K);
@@ -279,47 +284,11 @@ LB_API int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const v
                         void *stream);
 
 /*
- * Calibration kernels for the benchmark: what the machine sustains for the two bounds of the rooflines.  The
- * caller times them (HIP events on `stream`).
- *   lb_calib_valu     runs lb_calib_valu_lane_instr(iters) lane-instructions of independent chains on registers with
- *                     every wave slot of the device occupied; mix 0: the binary kernel's v_xor_b32 / v_bcnt_u32_b32
- *                     pair, mix 1: the ternary kernel's v_and_b32 / v_bitop3_b32 / 2 x v_bcnt_u32_b32.
- *   lb_calib_stream   mode 0: read `bytes` from src; 1: write `bytes` to dst; 2: copy src -> dst (128-bit accesses,
- *                     bytes a multiple of 16; src / dst may be NULL for the mode that does not use them).
- *   sink              device scratch owned by the caller, at least lb_calib_sink_bytes() bytes; receives per-thread
- *                     results so that the work cannot be optimized away.
- */
-LB_API size_t lb_calib_sink_bytes(void);
-LB_API int64_t lb_calib_valu_lane_instr(int64_t iters);
-LB_API int lb_calib_valu(int mix, int64_t iters, void *sink, void *stream);
-LB_API int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, void *sink, void *stream);
-
-/*
- * Tuning hook for benchmarks: force the tile variant used by one of the gemm_* entry points.
- *   op       0 = gemm_bnn, 1 = gemm_tnn, 2 = gemm_tbn (tile variant of the tiled kernel; forcing one also keeps
- *            skinny problems on the tiled kernel), 3 = configuration of the skinny (depth-split) kernel (forcing one
- *            also sends every product with at most 32 strings on one side to that kernel),
- *            4 = kernel instance of gemm_i8_mfma (0..2: 4-wave tiles 128x128, 256x256, 256x128; 3..5: wave-specialised
- *            256x128 with 3, 2, 4 depth steps of prefetch; 6: direct-to-LDS 256x128 with 64-byte depth stages;
- *            7, 8, 9: direct-to-LDS 256x128 / 128x128 / 64x64 tiles with 128-byte stages where the depth allows;
- *            an instance that cannot serve a shape falls back to the next simpler one),
- *            5 = kernel instance of gemm_u4_mfma and gemm_t4_mfma (0: 256x256 tile with 4 waves, 1: 256x256 with 8
- *            waves, 2: 128x128, 3: 64x64)
- *   variant  index into that op's variant table, or -1 to restore shape-based selection.
- * Returns LB_OK, or LB_EINVAL if op/variant is out of range.  lb_num_variants(op) gives the table size and
- * lb_variant_name(op, variant) a short description (host string owned by the library, NULL if out of range).
- * Process-wide; not meant to be changed while other threads are inside gemm_* calls.
- */
-LB_API int lb_set_variant(int op, int variant);
-
-/*
  * Which kernel a gemm_bnn / gemm_tnn / gemm_tbn call (c16 = 0) or a gemm_c16 call (c16 = 1) of this shape would run:
  * host logic only, usable without a GPU.  kind 0 = BNN, 1 = TNN, 2 = TBN.  Returns a short description (thread-local
  * host string, valid until the next call on the thread), or NULL for arguments the gemm calls would reject.
  */
 LB_API const char *lb_describe_plan(int kind, int64_t M, int64_t N, int64_t K, int c16);
-LB_API int lb_num_variants(int op);
-LB_API const char *lb_variant_name(int op, int variant);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
            "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
-           "lb_variant_name", "lb_describe_plan", "lb_calib_sink_bytes", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
+           "lb_variant_name", "lb_describe_plan", "lb_arch_supported", "lb_calib_sink_bytes", "lb_calib_clocks_bytes",
+           "lb_calib_wall_clock_khz", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
 
 class GemmProblem(ctypes.Structure):
@@ -93,11 +94,17 @@ def lib() -> ctypes.CDLL:
         L.lb_calib_sink_bytes.restype = ctypes.c_size_t
         L.lb_calib_sink_bytes.argtypes = []
         L.lb_calib_valu_lane_instr.restype = i64
-        L.lb_calib_valu_lane_instr.argtypes = [i64]
+        L.lb_calib_valu_lane_instr.argtypes = [ci, i64, ci]
         L.lb_calib_valu.restype = ci
-        L.lb_calib_valu.argtypes = [ci, i64, vp, vp]
+        L.lb_calib_valu.argtypes = [ci, i64, ci, vp, vp, vp]
+        L.lb_calib_clocks_bytes.restype = ctypes.c_size_t
+        L.lb_calib_clocks_bytes.argtypes = []
+        L.lb_calib_wall_clock_khz.restype = ci
+        L.lb_calib_wall_clock_khz.argtypes = []
+        L.lb_arch_supported.restype = ci
+        L.lb_arch_supported.argtypes = [ctypes.c_char_p]
         L.lb_calib_stream.restype = ci
-        L.lb_calib_stream.argtypes = [ci, vp, vp, i64, vp, vp]
+        L.lb_calib_stream.argtypes = [ci, vp, vp, i64, ci, vp, vp]
         L.lb_set_variant.restype = ci
         L.lb_set_variant.argtypes = [ci, ci]
         L.lb_num_variants.restype = ci
@@ -329,16 +336,29 @@ def lb_calib_sink_bytes() -> int:
     return lib().lb_calib_sink_bytes()
 
 
-def lb_calib_valu_lane_instr(iters: int) -> int:
-    return lib().lb_calib_valu_lane_instr(iters)
+def lb_calib_valu_lane_instr(mix: int, iters: int, waves_per_simd: int = 8) -> int:
+    return lib().lb_calib_valu_lane_instr(mix, iters, waves_per_simd)
 
 
-def lb_calib_valu(mix: int, iters: int, sink: torch.Tensor, stream=None) -> None:
-    _check(lib().lb_calib_valu(mix, iters, _ptr(sink), _stream(stream)))
+def lb_calib_valu(mix: int, iters: int, sink: torch.Tensor, clocks: Optional[torch.Tensor] = None,
+                  waves_per_simd: int = 8, stream=None) -> None:
+    _check(lib().lb_calib_valu(mix, iters, waves_per_simd, _ptr(sink), _ptr(clocks), _stream(stream)))
 
 
-def lb_calib_stream(mode: int, src, dst, nbytes: int, sink, stream=None) -> None:
-    _check(lib().lb_calib_stream(mode, _ptr(src), _ptr(dst), nbytes, _ptr(sink), _stream(stream)))
+def lb_calib_clocks_bytes() -> int:
+    return lib().lb_calib_clocks_bytes()
+
+
+def lb_calib_wall_clock_khz() -> int:
+    return lib().lb_calib_wall_clock_khz()
+
+
+def lb_arch_supported(arch: str) -> bool:
+    return bool(lib().lb_arch_supported(arch.encode()))
+
+
+def lb_calib_stream(mode: int, src, dst, nbytes: int, sink, blocks: int = 0, stream=None) -> None:
+    _check(lib().lb_calib_stream(mode, _ptr(src), _ptr(dst), nbytes, blocks, _ptr(sink), _stream(stream)))
 
 
 def lb_set_variant(op, variant: int) -> None:

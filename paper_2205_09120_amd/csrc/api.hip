@@ -6,13 +6,18 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/lowbit_gemm.h"
+#include "../../include/lowbit_gemm_bench.h"
 #include "lowbit_internal.h"
 
 namespace {
 
 thread_local char g_err[256] = "";
-int g_forced[3] = {-1, -1, -1};
+// benchmark hook (lb_set_variant): forced tile variant per gemm entry point; every call reads its slot once
+std::atomic<int> g_forced[3] = {{-1}, {-1}, {-1}};
+int forced_variant(int kind) { return g_forced[kind].load(std::memory_order_relaxed); }
 
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 int fail(int code, const char *fmt, ...)
@@ -22,6 +27,42 @@ int fail(int code, const char *fmt, ...)
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return code;
+}
+
+// The library holds machine code for gfx950 only.  Every entry point asks this before its first launch on a device
+// (the answer is cached per device), so that a call on another GPU fails with a clear status instead of a launch error.
+bool arch_supported(const char *arch)
+{
+    // "gfx950" alone or followed by feature flags ("gfx950:sramecc+:xnack-")
+    return arch && strncmp(arch, "gfx950", 6) == 0 && (arch[6] == '\0' || arch[6] == ':');
+}
+
+constexpr int kMaxDevices = 64;
+std::atomic<signed char> g_arch_state[kMaxDevices];  // 0 = not asked yet, 1 = gfx950, -1 = something else
+
+int check_device(const char *name)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(LB_EUNSUPPORTED, "%s: device index %d beyond %d", name, dev, kMaxDevices - 1);
+    signed char st = g_arch_state[dev].load(std::memory_order_relaxed);
+    if (st == 0) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess)
+            return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+        st = arch_supported(prop.gcnArchName) ? 1 : -1;
+        g_arch_state[dev].store(st, std::memory_order_relaxed);
+        if (st < 0)
+            return fail(LB_EUNSUPPORTED, "%s: device %d is %s; this library is built for gfx950 only", name, dev,
+                        prop.gcnArchName);
+    }
+    if (st < 0)
+        return fail(LB_EUNSUPPORTED, "%s: device %d is not gfx950; this library is built for gfx950 only", name, dev);
+    return LB_OK;
 }
 
 constexpr int64_t kMaxDepth = 0x7fffffffLL;    // int32 accumulators: |c| <= K must fit
@@ -89,6 +130,8 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
         return rc;
     if (packed_bytes(rows, K, ternary ? 16 : 8) == 0)
         return fail(LB_EOVERFLOW, "%s: packed size overflows", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e =
         lowbit::launch_pack(ternary, src, rows, K, stride_r, stride_k, dst, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -205,7 +248,8 @@ GemmPlan plan_gemm(int kind, int64_t M, int64_t N, int64_t K, bool c16)
     const int64_t KW = (K + 63) / 64;
     int count = 0;
     const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
-    const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
+    const int fv = forced_variant(kind);
+    const bool forced = fv >= 0 && fv < count;
 
     // Skinny problems (fully connected layers with a small batch) stream the large operand once and split the
     // depth across lanes.  A forced tile variant bypasses this path.
@@ -249,7 +293,7 @@ GemmPlan plan_gemm(int kind, int64_t M, int64_t N, int64_t K, bool c16)
             return p;
         }
     }
-    p.variant = forced ? g_forced[kind] : choose_variant(tab, count, rowsS, rowsV, KW);
+    p.variant = forced ? fv : choose_variant(tab, count, rowsS, rowsV, KW);
     return p;
 }
 
@@ -263,6 +307,8 @@ int do_gemm(int kind, const char *name, int64_t M, int64_t N, int64_t K, const u
         return rc;
     const int64_t KW = (K + 63) / 64;
     const GemmPlan p = plan_gemm(kind, M, N, K, c16);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     hipError_t e;
     if (p.path == GemmPlan::SKINNY) {
         const bool b_streamed = p.transposed;
@@ -349,6 +395,8 @@ extern "C" {
 const char *lb_last_error(void) { return g_err; }
 
 int lb_format_version(void) { return LB_FORMAT_VERSION; }
+
+int lb_arch_supported(const char *gcn_arch_name) { return arch_supported(gcn_arch_name) ? 1 : 0; }
 
 size_t packed_binary_bytes(int64_t rows, int64_t K) { return packed_bytes(rows, K, 8); }
 
@@ -469,6 +517,8 @@ int gemm_grouped(int kind, int64_t count, const void *table_dev, int64_t workgro
         return fail(LB_EINVAL, "%s: %lld workgroups for no problems", name, (long long)workgroups);
     if (!table_dev || !aligned(table_dev, 16))
         return fail(LB_EINVAL, "%s: table_dev must be a 16-byte aligned device pointer", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e =
         lowbit::launch_gemm_group(kind, static_cast<const lowbit::GroupHeader *>(table_dev), (uint32_t)count,
                                   (uint32_t)workgroups, static_cast<hipStream_t>(stream));
@@ -502,6 +552,8 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
         return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
     if (!aligned(C, 4))
         return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = lowbit::launch_gemm_i8(M, N, K, A, lda, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -549,8 +601,10 @@ int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t K, cons
     a.q_hi = hi;
     a.q_out = Out;
     a.q_planes = out_planes;
-    const bool forced = g_forced[kind] >= 0 && g_forced[kind] < count;
-    const int v = forced ? g_forced[kind] : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
+    const int fv = forced_variant(kind);
+    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = tab[v].launch_transposed(a);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -584,6 +638,8 @@ int gemm_u8_mfma(int64_t M, int64_t N, int64_t K, const uint8_t *A, int64_t lda,
         return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
     if (!aligned(C, 4))
         return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e =
         lowbit::launch_gemm_u8(M, N, K, A, lda, B, ldb, zA, zB, C, ldc, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -633,6 +689,8 @@ int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int6
     g.sw = stride_w;
     g.ph = pad_h;
     g.pw = pad_w;
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = lowbit::launch_im2col_packed(planes, Fp, Bp, g, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
@@ -657,6 +715,8 @@ int pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64
         return rc;
     if (!sums || !aligned(sums, 4))
         return fail(LB_EINVAL, "%s: sums must be a 4-byte aligned device pointer", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = lowbit::launch_pack_u4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
                                                 static_cast<uint8_t *>(dst), sums, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -690,6 +750,8 @@ int gemm_u4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const int32_t 
         return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
     if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(sumA, 4) || !aligned(sumB, 4) || !aligned(C, 4))
         return fail(LB_EINVAL, "%s: packed operands must be 16-byte aligned, sums and C 4-byte aligned", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e =
         lowbit::launch_gemm_u4(M, N, K, static_cast<const uint8_t *>(Ap), sumA, static_cast<const uint8_t *>(Bp), sumB,
                                zA, zB, C, ldc, static_cast<hipStream_t>(stream));
@@ -713,6 +775,8 @@ int pack_t4(const int8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_
     const int rc = check_pack(name, src, rows, K, stride_r, stride_k, dst, kT4MaxDepth, &nothing, &k_contig);
     if (rc != LB_OK || nothing)
         return rc;
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = lowbit::launch_pack_t4(src, rows, K, k_contig ? stride_r : 1, k_contig ? 1 : stride_k,
                                                 static_cast<uint8_t *>(dst), static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -743,6 +807,8 @@ int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const void *Bp
         return fail(LB_EOVERFLOW, "%s: M*ldc overflows", name);
     if (!aligned(Ap, 16) || !aligned(Bp, 16) || !aligned(C, 4))
         return fail(LB_EINVAL, "%s: packed operands must be 16-byte aligned, C 4-byte aligned", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
     const hipError_t e = lowbit::launch_gemm_t4(M, N, K, static_cast<const uint8_t *>(Ap), static_cast<const uint8_t *>(Bp),
                                                 C, ldc, static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
@@ -752,36 +818,58 @@ int gemm_t4_mfma(int64_t M, int64_t N, int64_t K, const void *Ap, const void *Bp
 
 size_t lb_calib_sink_bytes(void) { return (size_t)lowbit::calib_grid_blocks() * 2 * 256 * 4; }
 
-int64_t lb_calib_valu_lane_instr(int64_t iters) { return iters > 0 ? lowbit::calib_valu_lane_instr(iters) : 0; }
-
-int lb_calib_valu(int mix, int64_t iters, void *sink, void *stream)
+int64_t lb_calib_valu_lane_instr(int mix, int64_t iters, int waves_per_simd)
 {
-    if (mix != 0 && mix != 1)
-        return fail(LB_EINVAL, "lb_calib_valu: mix=%d must be 0 (xor, bcnt) or 1 (and, bitop3, bcnt, bcnt)", mix);
+    if (mix < 0 || mix >= lowbit::CALIB_NUM_MIXES || iters <= 0 || waves_per_simd < 1 || waves_per_simd > 8)
+        return 0;
+    return lowbit::calib_valu_lane_instr(mix, iters, waves_per_simd);
+}
+
+size_t lb_calib_clocks_bytes(void) { return (size_t)lowbit::calib_grid_blocks() * 2 * 8; }
+
+int lb_calib_wall_clock_khz(void) { return lowbit::calib_wall_clock_khz(); }
+
+int lb_calib_valu(int mix, int64_t iters, int waves_per_simd, void *sink, void *clocks, void *stream)
+{
+    const char *name = "lb_calib_valu";
+    if (mix < 0 || mix >= lowbit::CALIB_NUM_MIXES)
+        return fail(LB_EINVAL, "%s: mix=%d must lie in [0, %d)", name, mix, (int)lowbit::CALIB_NUM_MIXES);
     if (iters <= 0 || iters > (1 << 24))
-        return fail(LB_EINVAL, "lb_calib_valu: iters=%lld must lie in [1, 2^24]", (long long)iters);
+        return fail(LB_EINVAL, "%s: iters=%lld must lie in [1, 2^24]", name, (long long)iters);
+    if (waves_per_simd < 1 || waves_per_simd > 8)
+        return fail(LB_EINVAL, "%s: waves_per_simd=%d must lie in [1, 8]", name, waves_per_simd);
     if (!sink || !aligned(sink, 4))
-        return fail(LB_EINVAL, "lb_calib_valu: sink must be a 4-byte aligned device buffer");
-    const hipError_t e =
-        lowbit::launch_calib_valu(mix, (int)iters, static_cast<uint32_t *>(sink), static_cast<hipStream_t>(stream));
+        return fail(LB_EINVAL, "%s: sink must be a 4-byte aligned device buffer", name);
+    if (!aligned(clocks, 8))
+        return fail(LB_EINVAL, "%s: clocks must be NULL or an 8-byte aligned device buffer", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
+    const hipError_t e = lowbit::launch_calib_valu(mix, (int)iters, waves_per_simd, static_cast<uint32_t *>(sink),
+                                                   static_cast<unsigned long long *>(clocks),
+                                                   static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
-        return fail(LB_EHIP, "lb_calib_valu: %s", hipGetErrorString(e));
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;
 }
 
-int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, void *sink, void *stream)
+int lb_calib_stream(int mode, const void *src, void *dst, int64_t bytes, int blocks, void *sink, void *stream)
 {
+    const char *name = "lb_calib_stream";
     if (mode < 0 || mode > 2)
-        return fail(LB_EINVAL, "lb_calib_stream: mode=%d must be 0 (read), 1 (write) or 2 (copy)", mode);
+        return fail(LB_EINVAL, "%s: mode=%d must be 0 (read), 1 (write) or 2 (copy)", name, mode);
     if (bytes <= 0 || bytes % 16 != 0)
-        return fail(LB_EINVAL, "lb_calib_stream: bytes=%lld must be a positive multiple of 16", (long long)bytes);
+        return fail(LB_EINVAL, "%s: bytes=%lld must be a positive multiple of 16", name, (long long)bytes);
+    if (blocks < 0 || blocks > 2 * lowbit::calib_grid_blocks())
+        return fail(LB_EINVAL, "%s: blocks=%d must lie in [0, %d]", name, blocks, 2 * lowbit::calib_grid_blocks());
     if ((mode != 1 && (!src || !aligned(src, 16))) || (mode != 0 && (!dst || !aligned(dst, 16))) ||
         (mode == 0 && (!sink || !aligned(sink, 4))))
-        return fail(LB_EINVAL, "lb_calib_stream: missing or misaligned buffer for mode %d", mode);
-    const hipError_t e = lowbit::launch_calib_stream(mode, src, dst, bytes, static_cast<uint32_t *>(sink),
+        return fail(LB_EINVAL, "%s: missing or misaligned buffer for mode %d", name, mode);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
+    const hipError_t e = lowbit::launch_calib_stream(mode, src, dst, bytes, blocks, static_cast<uint32_t *>(sink),
                                                      static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
-        return fail(LB_EHIP, "lb_calib_stream: %s", hipGetErrorString(e));
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;
 }
 
@@ -831,7 +919,7 @@ int lb_set_variant(int op, int variant)
         return fail(LB_EINVAL, "lb_set_variant: op=%d out of range", op);
     if (variant < -1 || variant >= count)
         return fail(LB_EINVAL, "lb_set_variant: variant=%d out of range [-1,%d)", variant, count);
-    g_forced[op] = variant;
+    g_forced[op].store(variant, std::memory_order_relaxed);
     return LB_OK;
 }
 

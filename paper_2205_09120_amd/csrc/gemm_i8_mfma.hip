@@ -29,6 +29,7 @@
 // tiles, as sums of the unsigned bytes (v_sad_u8 against zero, 4 bytes per instruction) minus 128 per byte, and
 // combined through LDS after the depth loop.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 
 #include <type_traits>
@@ -1118,17 +1119,18 @@ hipError_t launch_dl_auto(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     return launch_dl_tile<U8, 1, 1>(M, N, K, A, lda, B, ldb, C, ldc, stream, zA, zB);
 }
 
-int g_i8_forced = -1;
+std::atomic<int> g_i8_forced{-1};  // benchmark hook; read once per call
 
 }  // namespace
 
-void i8_force_tile(int t) { g_i8_forced = t; }
+void i8_force_tile(int t) { g_i8_forced.store(t, std::memory_order_relaxed); }
 
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                           int32_t *C, int64_t ldc, hipStream_t stream)
 {
     const int64_t tiles = ((M + 255) / 256) * ((N + 127) / 128);
-    int t = g_i8_forced;
+    const int forced = g_i8_forced.load(std::memory_order_relaxed);
+    int t = forced;
     // a right operand of at most 16 columns would leave a matrix-core tile almost empty: stream A with dot products
     if (t < 0 && N <= 16 && M >= 64)
         return launch_gemm_i8_skinny(M, N, K, A, lda, B, ldb, C, ldc, stream);
@@ -1161,7 +1163,7 @@ hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int6
     if (t == 2)
         return launch_tile<4, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     // unforced small problems: 64 x 64 tiles put four times as many workgroups on the machine
-    if (g_i8_forced < 0 && ((M + 127) / 128) * ((N + 127) / 128) < 128)
+    if (forced < 0 && ((M + 127) / 128) * ((N + 127) / 128) < 128)
         return launch_tile<1, 1, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
     return launch_tile<2, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream, 0, 0);
 }

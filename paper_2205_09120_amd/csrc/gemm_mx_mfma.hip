@@ -19,6 +19,7 @@
 // fragment, on the same instruction at its 4-bit rate: what the matrix cores of this chip do with the operands that
 // the paper multiplies with AND / XOR / popcount (pack_t4, gemm_t4_mfma).
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <type_traits>
 
@@ -37,7 +38,7 @@ constexpr int kScaleOne = (int)0x7f7f7f7fu;  // block scale 1
 constexpr int kComputeUnits = 256;           // MI355X
 constexpr int kFrag4Bytes = 1024;            // 4-bit floats: 32 rows x 64 depth positions x 4 bits
 
-int g_u4_forced = -1;
+std::atomic<int> g_u4_forced{-1};  // benchmark hook; read once per call
 
 // -------------------------------------------------------------------------------------------------- packing
 
@@ -614,8 +615,9 @@ template <int FMT>
 hipError_t launch_mx_auto(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, const int32_t *sumA, const uint8_t *Bp,
                           const int32_t *sumB, int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream)
 {
-    if (g_u4_forced >= 0)
-        return launch_mx_instance<FMT>(g_u4_forced, M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
+    const int forced = g_u4_forced.load(std::memory_order_relaxed);
+    if (forced >= 0)
+        return launch_mx_instance<FMT>(forced, M, N, K, Ap, sumA, Bp, sumB, zA, zB, C, ldc, stream);
     const int64_t nMB = (M + 255) / 256, nNB = (N + 255) / 256;
     const int64_t t256 = nMB * nNB, t128 = ((M + 127) / 128) * ((N + 127) / 128);
     const int inst = t256 >= 128 ? 1 : t128 >= 128 ? 2 : 3;
@@ -640,7 +642,7 @@ hipError_t launch_mx_auto(int64_t M, int64_t N, int64_t K, const uint8_t *Ap, co
 }  // namespace
 
 int u4_num_instances() { return 4; }
-void u4_force_instance(int t) { g_u4_forced = t; }
+void u4_force_instance(int t) { g_u4_forced.store(t, std::memory_order_relaxed); }
 
 hipError_t launch_pack_u4(const uint8_t *src, int64_t rows, int64_t K, int64_t stride_r, int64_t stride_k,
                           uint8_t *dst, int32_t *sums, hipStream_t stream)

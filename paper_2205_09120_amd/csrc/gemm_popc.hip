@@ -590,6 +590,9 @@ hipError_t launch_splitk(const GemmArgs &a, bool transposed, int nsplit)
     if (tiles > 0x7fffffffLL || nz > 65535 || M > 65535)
         return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(clear_c_kernel, dim3((unsigned)((N + 255) / 256), (unsigned)M), dim3(256), 0, a.stream, a.C, a.ldc, N);
+    const hipError_t ec = hipGetLastError();
+    if (ec != hipSuccess)  // without the cleared C the partial sums must not be added
+        return ec;
     hipLaunchKernelGGL((gemm_popc_splitk_kernel<KIND, TS, TV, WAVES, KG, SG>), dim3((unsigned)tiles, (unsigned)nz),
                        dim3(64 * WAVES), 0, a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB,
                        transposed ? 1 : 0, wps);

@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "lowbit_internal.h"
 
 namespace lowbit {
@@ -262,14 +264,14 @@ template <int KIND, int R, int WAVES, bool TR, int NS = 8> hipError_t launch_sk(
     return hipGetLastError();
 }
 
-int g_skinny_forced = -1;
+std::atomic<int> g_skinny_forced{-1};  // benchmark hook; read once per call
 
 template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
 {
     // (rows per wave, waves per workgroup), measured on M x 4096 .. 65536 x 1 .. 16 problems: large row counts
     // stream best with 2 rows per wave (binary operands, half the bytes per row: 4); a few thousand rows are
     // latency-bound and want many small waves in flight
-    int cfg = g_skinny_forced;
+    int cfg = g_skinny_forced.load(std::memory_order_relaxed);
     if (cfg < 0) {
         if (a.rowsX >= 16384)
             cfg = (KIND == KIND_BNN || KIND == KIND_TBN_SV) ? 7 : KIND == KIND_TNN ? 3 : 1;
@@ -314,8 +316,8 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
 }  // namespace
 
 int skinny_num_configs() { return 8; }
-void skinny_force_config(int cfg) { g_skinny_forced = cfg; }
-int skinny_forced_config() { return g_skinny_forced; }
+void skinny_force_config(int cfg) { g_skinny_forced.store(cfg, std::memory_order_relaxed); }
+int skinny_forced_config() { return g_skinny_forced.load(std::memory_order_relaxed); }
 
 hipError_t launch_gemm_skinny(int kind, const SkinnyArgs &a, bool transposed)
 {

@@ -102,11 +102,21 @@ struct Im2colGeom {
 };
 hipError_t launch_im2col_packed(int planes, const uint64_t *Fp, uint64_t *Bp, const Im2colGeom &g, hipStream_t stream);
 
-// Calibration kernels (calibrate.hip).  sink needs calib_grid_blocks()*2*256 dwords.
+// Calibration kernels (calibrate.hip).  sink needs calib_grid_blocks()*2*256 dwords (mode 0 of the stream kernel:
+// blocks*256 dwords when a grid size is given).
+// VALU instruction mixes: the three kernels' own (binary, ternary, ternary-binary) and single instruction forms.
+enum CalibMix { CALIB_BNN = 0, CALIB_TNN = 1, CALIB_TBN = 2, CALIB_XOR_VV = 3, CALIB_AND_SV = 4, CALIB_BITOP_SVV = 5,
+                CALIB_BCNT = 6, CALIB_NUM_MIXES = 7 };
 int calib_grid_blocks();
-int64_t calib_valu_lane_instr(int64_t iters);
-hipError_t launch_calib_valu(int mix, int iters, uint32_t *sink, hipStream_t stream);
-hipError_t launch_calib_stream(int mode, const void *src, void *dst, int64_t bytes, uint32_t *sink, hipStream_t stream);
+int64_t calib_valu_lane_instr(int mix, int64_t iters, int waves_per_simd);
+// clocks: nullptr, or 2 x 256 x waves_per_simd 64-bit values: per workgroup the ticks of the shader-clock counter and
+// of the constant-rate counter (calib_wall_clock_khz() ticks per millisecond) that passed while its first wave ran
+hipError_t launch_calib_valu(int mix, int iters, int waves_per_simd, uint32_t *sink, unsigned long long *clocks,
+                             hipStream_t stream);
+int calib_wall_clock_khz();  // 0 if the runtime does not report it
+// blocks: grid size of the streaming kernel (workgroups of 256 threads), 0 = the default of 16 per compute unit
+hipError_t launch_calib_stream(int mode, const void *src, void *dst, int64_t bytes, int blocks, uint32_t *sink,
+                               hipStream_t stream);
 
 // int8 matrix-core GEMM launcher (gemm_i8_mfma.hip).
 hipError_t launch_gemm_i8(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,

@@ -20,7 +20,8 @@ def L():
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "lowbit_gemm.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     return sorted(set(re.findall(r"LB_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)))
 
 
@@ -179,15 +180,20 @@ def test_requant_argument_validation(L):
 
 def test_calibration_argument_validation(L):
     fake = 0x1000
-    assert L.lb_calib_sink_bytes() > 0
-    assert L.lb_calib_valu_lane_instr(1) > 0 and L.lb_calib_valu_lane_instr(0) == 0
-    assert L.lb_calib_valu(0, 0, fake, None) == binding.LB_EINVAL
-    assert L.lb_calib_valu(0, 10, None, None) == binding.LB_EINVAL
-    assert L.lb_calib_valu(2, 10, fake, None) == binding.LB_EINVAL
-    assert L.lb_calib_stream(3, fake, fake, 16, fake, None) == binding.LB_EINVAL
-    assert L.lb_calib_stream(2, fake, fake, 15, fake, None) == binding.LB_EINVAL
-    assert L.lb_calib_stream(0, None, None, 16, fake, None) == binding.LB_EINVAL
-    assert L.lb_calib_stream(1, None, None, 16, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_sink_bytes() > 0 and L.lb_calib_clocks_bytes() > 0
+    assert L.lb_calib_valu_lane_instr(0, 1, 8) > 0 and L.lb_calib_valu_lane_instr(0, 0, 8) == 0
+    assert L.lb_calib_valu_lane_instr(1, 10, 4) == 2 * L.lb_calib_valu_lane_instr(0, 10, 4)   # 4 against 2 per unit
+    assert L.lb_calib_valu_lane_instr(7, 10, 4) == 0 and L.lb_calib_valu_lane_instr(0, 10, 9) == 0
+    assert L.lb_calib_valu(0, 0, 8, fake, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(0, 10, 8, None, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(7, 10, 8, fake, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(0, 10, 0, fake, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_valu(0, 10, 8, fake, fake + 4, None) == binding.LB_EINVAL     # misaligned clock buffer
+    assert L.lb_calib_stream(3, fake, fake, 16, 0, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(2, fake, fake, 15, 0, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(0, None, None, 16, 0, fake, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(1, None, None, 16, 0, None, None) == binding.LB_EINVAL
+    assert L.lb_calib_stream(0, fake, None, 16, -1, fake, None) == binding.LB_EINVAL
 
 
 def test_variant_hooks(L):
@@ -314,3 +320,12 @@ def test_dispatch_plan_is_host_logic(L):
         assert d("tnn", 4096, 8, 16384) == "tnn tiled kernel [KIND_TNN ts4 tv1 w4 kg16 sg4], B on the scalar side"
     finally:
         L.lb_set_variant(1, -1)
+
+
+def test_arch_check_is_host_logic(L):
+    """Only gfx950 devices are served: the rule every entry point applies before its first launch on a device."""
+    assert binding.lb_arch_supported("gfx950")
+    assert binding.lb_arch_supported("gfx950:sramecc+:xnack-")
+    for other in ("gfx942", "gfx942:sramecc+:xnack-", "gfx90a", "gfx9500", "gfx95", "", "sm_90"):
+        assert not binding.lb_arch_supported(other), other
+    assert L.lb_arch_supported(None) == 0

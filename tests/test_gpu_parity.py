@@ -500,19 +500,41 @@ def test_u8_extreme_values_and_depth_limit():
 def test_calibration_kernels_run_and_copy_is_exact():
     say("calibration kernels")
     sink = torch.zeros(lb.lb_calib_sink_bytes() // 4, dtype=torch.int32, device="cuda")
-    lb.lb_calib_valu(1, 8, sink)
+    clk = torch.zeros(lb.lb_calib_clocks_bytes() // 8, dtype=torch.int64, device="cuda")
+    iters, seed = 8, 0x9e3779b9
+    # what every thread of the binary and the popcount-only chain must have counted: 8 chains, a[c] = seed*(c+1) + thread,
+    # s[c] = (seed >> c) ^ (workgroup * (c+3)), in 32-bit arithmetic
+    blk = np.arange(2048, dtype=np.uint64)[:, None, None]
+    tid = np.arange(256, dtype=np.uint64)[None, :, None]
+    c = np.arange(8, dtype=np.uint64)[None, None, :]
+    a = (seed * (c + 1) + tid) & 0xffffffff
+    sc = ((seed >> c) ^ (blk * (c + 3))) & 0xffffffff
+    popc = lambda x: np.array([bin(int(v)).count("1") for v in x.ravel()]).reshape(x.shape)
+    want_bcnt = np.broadcast_to(popc(a).sum(axis=2) * iters, (2048, 256))
+    for waves in (8, 3):
+        nthreads = 256 * waves * 256
+        sink.zero_()
+        lb.lb_calib_valu(6, iters, sink, clk, waves)
+        torch.cuda.synchronize()
+        assert np.array_equal(sink.cpu().numpy()[:nthreads].reshape(-1, 256), want_bcnt[: 256 * waves])
+        assert not sink.cpu().numpy()[nthreads:].any()
+        ck = clk.cpu().numpy().reshape(-1, 2)[: 256 * waves]
+        assert (ck > 0).all()                                   # both counters advanced in every workgroup
+    lb.lb_calib_valu(0, iters, sink, None, 1)
     torch.cuda.synchronize()
-    assert sink.cpu().numpy()[: 2048 * 256].any()
-    lb.lb_calib_valu(0, 8, sink)
+    x = a[:, :, :] ^ sc[:256]
+    want = np.array([[sum(bin(int(v)).count("1") for v in x[b, t]) for t in range(256)] for b in range(4)]) * iters
+    assert np.array_equal(sink.cpu().numpy()[: 4 * 256].reshape(4, 256), want)
+    for mix in (1, 2, 3, 4, 5):
+        lb.lb_calib_valu(mix, iters, sink, clk)
     torch.cuda.synchronize()
-    # every thread accumulates popcounts of 8 * 16 32-bit words: 0 <= sum <= 8*16*32, and some are non-zero
-    s = sink.cpu().numpy()[: 2048 * 256]
-    assert s.min() >= 0 and s.max() <= 8 * 16 * 32 and s.any()
+    assert lb.lb_calib_valu_lane_instr(1, iters, 8) == 2048 * 256 * iters * 32
     n = 1 << 20
     src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda")
     dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
     lb.lb_calib_stream(2, src, dst, n, sink)
     lb.lb_calib_stream(0, src, None, n, sink)
+    lb.lb_calib_stream(0, src, None, n, sink, 256)
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
     lb.lb_calib_stream(1, None, dst, n, sink)
