@@ -204,6 +204,29 @@ LB_API int gemm_grouped_plan(int kind, int64_t count, const lb_gemm_problem *pro
 LB_API int gemm_grouped(int kind, int64_t count, const void *table_dev, int64_t workgroups, void *stream);
 
 /*
+ * gemm_grouped_static -- gemm_grouped for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the launch table lives in an array inside the library instead
+ * of a device buffer the caller provides.
+ *
+ *   table_host   HOST memory: the table gemm_grouped_plan wrote for (kind, count, problems); table_bytes its size as
+ *                returned by gemm_grouped_table_bytes.  It is read during the call only (its contents travel to the
+ *                device inside kernel arguments), so it may be reused or freed as soon as the call returns.
+ *   limits       table_bytes <= gemm_grouped_static_max_bytes() (64 KiB: e.g. 512 problems of 16 tiles each);
+ *                a larger table is LB_EUNSUPPORTED and nothing is enqueued.  Each GPU the library runs on holds one
+ *                such array until the process ends.
+ *   The call enqueues ceil(table_bytes / 3584) small upload kernels and the group kernel on `stream`; it calls no
+ *   allocating or freeing routine and no memory copy.  Results are those of gemm_grouped on the same table.
+ *   Every call on a GPU uses that GPU's one array: calls whose work may overlap on one GPU (different streams, or
+ *   several threads without ordering between their streams) race on it and must be serialised by the caller; calls on
+ *   one stream are ordered and safe.  The array keeps the last call's table; nothing in it needs clearing, since a call
+ *   overwrites every byte its kernel reads.
+ * Errors: as gemm_grouped, plus LB_EINVAL when the table does not match kind / count / workgroups.
+ */
+LB_API size_t gemm_grouped_static_max_bytes(void);
+LB_API int gemm_grouped_static(int kind, int64_t count, const void *table_host, size_t table_bytes,
+                               int64_t workgroups, void *stream);
+
+/*
  * gemm_i8_mfma -- the same product C = A B from UNPACKED int8 operands with int32 accumulation on the
  * integer matrix cores.  It plays the role the 8-bit gemmlowp multiplication (U8, Section IV, Table II/III)
  * plays in the paper: the comparison point for the low-bit kernels.  Any int8 values are allowed.

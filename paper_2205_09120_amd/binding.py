@@ -21,7 +21,7 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
-           "gemm_grouped_plan", "gemm_grouped", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
+           "gemm_grouped_plan", "gemm_grouped", "gemm_grouped_static", "gemm_grouped_static_max_bytes", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_describe_plan", "lb_arch_supported", "lb_calib_sink_bytes", "lb_calib_clocks_bytes",
            "lb_calib_wall_clock_khz", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.gemm_grouped_plan.argtypes = [ci, i64, vp, vp, ctypes.c_size_t, ctypes.POINTER(i64)]
         L.gemm_grouped.restype = ci
         L.gemm_grouped.argtypes = [ci, i64, vp, i64, vp]
+        L.gemm_grouped_static_max_bytes.restype = ctypes.c_size_t
+        L.gemm_grouped_static_max_bytes.argtypes = []
+        L.gemm_grouped_static.restype = ci
+        L.gemm_grouped_static.argtypes = [ci, i64, vp, ctypes.c_size_t, i64, vp]
         L.im2col_packed.restype = ci
         L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
         L.gemm_i8_mfma.restype = ci
@@ -254,6 +258,17 @@ def gemm_grouped(kind, count: int, table_dev: Optional[torch.Tensor], workgroups
     _check(lib().gemm_grouped(_OPS.get(kind, kind), count, _ptr(table_dev), workgroups, _stream(stream)))
 
 
+def gemm_grouped_static_max_bytes() -> int:
+    return lib().gemm_grouped_static_max_bytes()
+
+
+def gemm_grouped_static(kind, count: int, table_host: Optional[torch.Tensor], workgroups: int, stream=None) -> None:
+    """Launch a planned group from its HOST table (uint8 CPU tensor); the device copy lives inside the library."""
+    nbytes = 0 if table_host is None else table_host.numel()
+    _check(lib().gemm_grouped_static(_OPS.get(kind, kind), count, _ptr(table_host), nbytes, workgroups,
+                                     _stream(stream)))
+
+
 def gemm_requant(kind, out_planes: int, M, N, K, Ap, Bp, lo, hi=None, Out=None, stream=None):
     """Thresholded product written as N packed strings of depth M (1 = binary, 2 = ternary planes)."""
     if Out is None:
@@ -405,11 +420,16 @@ class GemmGroup:
         probs = [GemmProblem(M, N, K, _ptr(Ap) or None, _ptr(Bp) or None, _ptr(C) or None,
                              C.stride(0) if C.dim() == 2 and C.numel() else max(N, 1))
                  for (M, N, K), (Ap, Bp), C in zip(self.shapes, self.operands, self.Cs)]
-        table, self.workgroups = gemm_grouped_plan(kind, probs)
-        self.table_dev = table.to(dev)
+        self.table_host, self.workgroups = gemm_grouped_plan(kind, probs)
+        self.table_dev = self.table_host.to(dev)
 
     def run(self, stream=None):
         gemm_grouped(self.kind, len(self.shapes), self.table_dev, self.workgroups, stream)
+        return self.Cs
+
+    def run_static(self, stream=None):
+        """The same launch through the entry point that keeps the table in the library's own device array."""
+        gemm_grouped_static(self.kind, len(self.shapes), self.table_host, self.workgroups, stream)
         return self.Cs
 
 

@@ -527,6 +527,48 @@ int gemm_grouped(int kind, int64_t count, const void *table_dev, int64_t workgro
     return LB_OK;
 }
 
+size_t gemm_grouped_static_max_bytes(void) { return lowbit::kGroupStaticBytes; }
+
+int gemm_grouped_static(int kind, int64_t count, const void *table_host, size_t table_bytes, int64_t workgroups,
+                        void *stream)
+{
+    const char *name = "gemm_grouped_static";
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    if (count < 0 || workgroups < 0)
+        return fail(LB_EINVAL, "%s: count=%lld workgroups=%lld must be >= 0", name, (long long)count,
+                    (long long)workgroups);
+    if (count > 0x7fffffffLL || workgroups > 0x7fffffffLL)
+        return fail(LB_EOVERFLOW, "%s: count=%lld workgroups=%lld exceed 2^31-1", name, (long long)count,
+                    (long long)workgroups);
+    if (workgroups == 0)
+        return LB_OK;
+    if (count == 0)
+        return fail(LB_EINVAL, "%s: %lld workgroups for no problems", name, (long long)workgroups);
+    if (!table_host)
+        return fail(LB_EINVAL, "%s: table_host is null", name);
+    // the table must be the one gemm_grouped_plan wrote for these values: its size follows from them
+    const size_t need = group_table_bytes(count, workgroups);
+    if (table_bytes != need)
+        return fail(LB_EINVAL, "%s: table_bytes=%zu, but a table of %lld problems and %lld workgroups has %zu", name,
+                    table_bytes, (long long)count, (long long)workgroups, need);
+    if (table_bytes > lowbit::kGroupStaticBytes)
+        return fail(LB_EUNSUPPORTED, "%s: table of %zu bytes exceeds the library's %zu-byte array (use gemm_grouped)",
+                    name, table_bytes, (size_t)lowbit::kGroupStaticBytes);
+    const auto *hdr = static_cast<const lowbit::GroupHeader *>(table_host);
+    if (hdr->magic != lowbit::kGroupMagic || hdr->kind != (uint32_t)kind || hdr->count != (uint32_t)count ||
+        hdr->workgroups != (uint32_t)workgroups)
+        return fail(LB_EINVAL, "%s: the table was not planned for kind=%d count=%lld workgroups=%lld", name, kind,
+                    (long long)count, (long long)workgroups);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
+    const hipError_t e = lowbit::launch_gemm_group_static(kind, table_host, table_bytes, (uint32_t)count,
+                                                          (uint32_t)workgroups, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
 int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                  int32_t *C, int64_t ldc, void *stream)
 {

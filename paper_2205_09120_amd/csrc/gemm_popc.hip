@@ -27,7 +27,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
+#include <string.h>
 
 #include "lowbit_internal.h"
 
@@ -681,7 +683,77 @@ const GemmVariant kTbnSv[] = {
     LB_SMALL(1200, 0, KIND_TBN_SV, 4, 1, 8, 16, 4),
 };
 
+// ---- launch table held by the library, for callers that cannot allocate device memory ----
+//
+// `scratch` is one table-sized array per GPU (each device that loads the code object holds its own copy until the
+// process ends).  In host code the array's name is only a handle for hipGetSymbolAddress: the device address it yields
+// is looked up once per device, with that device current, and used from then on wherever host code names the memory.
+static __device__ __align__(256) unsigned char scratch[kGroupStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+hipError_t group_scratch_ptr(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return e;
+        if (p == nullptr)
+            return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    *out = p;
+    return hipSuccess;
+}
+
+// A piece of the host-built table travels to the device inside the kernel arguments (copied by the runtime when the
+// launch is enqueued, so the host table may be reused or freed right after the call, and the launch can be captured).
+struct TableChunk {
+    uint4 q[kGroupChunkBytes / 16];
+};
+__global__ __launch_bounds__(kGroupChunkBytes / 16) void group_table_upload_kernel(uint4 *__restrict__ dst,
+                                                                                  const TableChunk chunk, int n16)
+{
+    const int i = threadIdx.x;
+    if (i < n16)
+        dst[i] = chunk.q[i];
+}
+
 }  // namespace
+
+hipError_t launch_gemm_group_static(int kind, const void *table_host, size_t table_bytes, uint32_t count,
+                                    uint32_t workgroups, hipStream_t stream)
+{
+    if (table_bytes == 0 || table_bytes % 16 != 0 || table_bytes > kGroupStaticBytes)
+        return hipErrorInvalidValue;
+    void *dev_table = nullptr;
+    hipError_t e = group_scratch_ptr(&dev_table);
+    if (e != hipSuccess)
+        return e;
+    const unsigned char *src = static_cast<const unsigned char *>(table_host);
+    for (size_t off = 0; off < table_bytes; off += kGroupChunkBytes) {
+        const size_t n = table_bytes - off < kGroupChunkBytes ? table_bytes - off : kGroupChunkBytes;
+        TableChunk chunk;
+        memcpy(chunk.q, src + off, n);
+        if (n < kGroupChunkBytes)
+            memset(reinterpret_cast<unsigned char *>(chunk.q) + n, 0, kGroupChunkBytes - n);
+        hipLaunchKernelGGL(group_table_upload_kernel, dim3(1), dim3(kGroupChunkBytes / 16), 0, stream,
+                           reinterpret_cast<uint4 *>(static_cast<unsigned char *>(dev_table) + off), chunk,
+                           (int)(n / 16));
+        e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+    }
+    return launch_gemm_group(kind, static_cast<const GroupHeader *>(dev_table), count, workgroups, stream);
+}
 
 hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
                              hipStream_t stream)

@@ -72,6 +72,13 @@ struct GroupRecord {
 static_assert(sizeof(GroupHeader) == 16 && sizeof(GroupRecord) == 64, "table layout is part of the host/device contract");
 hipError_t launch_gemm_group(int kind, const GroupHeader *table_dev, uint32_t count, uint32_t workgroups,
                              hipStream_t stream);
+// The same launch with the table in the library's own per-device array instead of caller memory: the HOST table is
+// uploaded in pieces of kGroupChunkBytes through kernel arguments (no allocation, no memcpy call), then the group
+// kernel runs on it.  table_bytes must be a positive multiple of 16 and at most kGroupStaticBytes.
+constexpr size_t kGroupStaticBytes = 64 * 1024;
+constexpr size_t kGroupChunkBytes = 3584;
+hipError_t launch_gemm_group_static(int kind, const void *table_host, size_t table_bytes, uint32_t count,
+                                    uint32_t workgroups, hipStream_t stream);
 
 // Skinny launch (gemm_skinny.hip): X is the large streamed operand, Y the small one (any count; processed 8, 16 or
 // 32 strings at a time: X is streamed once for up to 32).  Product (x, y) goes to C[x*ldc + y], or C[y*ldc + x] when transposed.

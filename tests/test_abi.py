@@ -322,6 +322,28 @@ def test_dispatch_plan_is_host_logic(L):
         L.lb_set_variant(1, -1)
 
 
+def test_grouped_static_argument_validation(L):
+    """The allocation-free grouped launch checks its table on the host before any HIP call."""
+    P = binding.GemmProblem
+    ok = P(20, 30, 100, 0x1000, 0x2000, 0x3000, 30)
+    table, wg = binding.gemm_grouped_plan("tnn", [ok])
+    n = table.numel()
+    assert L.gemm_grouped_static_max_bytes() == 64 * 1024
+    assert L.gemm_grouped_static(1, 0, None, 0, 0, None) == binding.LB_OK                    # nothing to do
+    assert L.gemm_grouped_static(7, 1, table.data_ptr(), n, wg, None) == binding.LB_EINVAL   # kind
+    assert L.gemm_grouped_static(1, 1, None, n, wg, None) == binding.LB_EINVAL               # null table
+    assert L.gemm_grouped_static(1, 1, table.data_ptr(), n + 16, wg, None) == binding.LB_EINVAL   # size mismatch
+    assert L.gemm_grouped_static(0, 1, table.data_ptr(), n, wg, None) == binding.LB_EINVAL   # planned for TNN
+    assert L.gemm_grouped_static(1, -1, table.data_ptr(), n, wg, None) == binding.LB_EINVAL
+    assert L.gemm_grouped_static(1, 1, table.data_ptr(), n, 2 ** 31, None) == binding.LB_EOVERFLOW
+    # a table beyond the library's array is refused with a clear message, nothing is enqueued
+    many = [P(16, 64, 64, 0x1000, 0x2000, 0x3000 + 0x10000 * i, 64) for i in range(1100)]
+    big, wgb = binding.gemm_grouped_plan("bnn", many)
+    assert big.numel() > 64 * 1024
+    assert L.gemm_grouped_static(0, len(many), big.data_ptr(), big.numel(), wgb, None) == binding.LB_EUNSUPPORTED
+    assert b"exceeds" in L.lb_last_error()
+
+
 def test_arch_check_is_host_logic(L):
     """Only gfx950 devices are served: the rule every entry point applies before its first launch on a device."""
     assert binding.lb_arch_supported("gfx950")
