@@ -253,6 +253,373 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
     }
 }
 
+// One 64-bit depth word of X against the same word of Y, added to the partial sums of one (row, string) pair.
+// x and y hold (nz, neg) planes when ternary (two dwords per plane) and the sign bits when binary.
+template <int KIND, typename XW, typename YW>
+__device__ __forceinline__ void sk_mac(int32_t &a0, int32_t &a1, const XW &x, const YW &y)
+{
+    if constexpr (KIND == KIND_BNN) {
+        popc_acc(a0, xor_vv(x.x, y.x));
+        popc_acc(a0, xor_vv(x.y, y.y));
+    } else if constexpr (KIND == KIND_TNN) {
+        const uint32_t m0 = and_vv(x.x, y.x), m1 = and_vv(x.y, y.y);
+        const uint32_t u0 = xor_and_vvv(x.z, y.z, m0), u1 = xor_and_vvv(x.w, y.w, m1);
+        popc_acc(a0, m0);
+        popc_acc(a1, u0);
+        popc_acc(a0, m1);
+        popc_acc(a1, u1);
+    } else if constexpr (KIND == KIND_TBN) {
+        popc_acc(a0, xor_and_vvv(x.z, y.x, x.x));
+        popc_acc(a0, xor_and_vvv(x.w, y.y, x.y));
+    } else {
+        popc_acc(a0, xor_and_vvv(y.z, x.x, y.x));
+        popc_acc(a0, xor_and_vvv(y.w, x.y, y.y));
+    }
+}
+
+// Streaming variant for at most NS short strings whose whole depth fits in LDS: Y is staged ONCE per workgroup, the
+// grid is at most two workgroups per compute unit, and every wave walks over its row groups (R rows each) with a ring
+// of D lane-steps of X in flight -- the loads of step s + D are issued right after step s has been multiplied, so the
+// HBM stream never waits for a barrier or for the cross-lane reduction of a finished row.  A lane-step is one 16-byte
+// load per lane and row: one depth word of a ternary string, two of a binary one (W), i.e. SW = 64 * W depth words per
+// wave and step; a row has JWn = ceil(KW / SW) steps and the ring runs on across row boundaries.  Every wave that has
+// work must have at least D steps.  The last round of Y loads is issued
+// BEFORE the first X loads and waited for with those still in flight, so a short stream (one row per wave: the
+// batch-8 fully connected layer) multiplies its first words while the rest of the row is still arriving.
+// LDS layout of Y: entry (step jb, string n, word w of the step) at ((jb * NS + n) * SW + slot(w)); slot(w) = w, except
+// for ternary Y next to binary X, where the two words a lane needs are 64 entries apart (conflict-free 16-byte reads).
+template <int KIND, int R, int WAVES, bool TR, int NS, bool KFULL, int D>
+__global__ __launch_bounds__(64 * WAVES) void gemm_skinny_stream_kernel(const void *__restrict__ Xp_,
+                                                                        const void *__restrict__ Yp_, int rowsX,
+                                                                        int rowsY, int KW, int K,
+                                                                        int32_t *__restrict__ C, int64_t ldc, int c16,
+                                                                        int JWn, int groups)
+{
+    using T = SkTraits<KIND>;
+    using YE = typename T::Y;
+    constexpr bool XBIN = sizeof(typename T::X) == 8;
+    constexpr bool YTER = sizeof(YE) == 16;
+    constexpr int W = XBIN ? 2 : 1;
+    constexpr int SW = 64 * W;
+    constexpr int NT = 64 * WAVES;
+    constexpr int V = R * NS;
+    constexpr int YU = 4;  // Y entries a thread stages per round
+    static_assert((V & (V - 1)) == 0 && V <= 64 && V >= 2, "R*NS must be a power of two <= 64");
+    static_assert((NS & (NS - 1)) == 0, "NS must be a power of two");
+
+    extern __shared__ uint4 sk_smem[];
+    YE *ylds = reinterpret_cast<YE *>(sk_smem);
+    const int entries = JWn * NS * SW;
+    int32_t *ynnz = reinterpret_cast<int32_t *>(ylds + entries);  // TBN_SV: non-zero positions of each Y string
+
+    const YE *__restrict__ Yp = static_cast<const YE *>(Yp_);
+    const uint4 *__restrict__ Xq = static_cast<const uint4 *>(Xp_);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int y0 = blockIdx.y * NS;
+    const int rstride = XBIN ? KW / 2 : KW;  // 16-byte pieces per X string (binary: KW is even)
+
+    if constexpr (KIND == KIND_TBN_SV) {
+        if (tid < NS)
+            ynnz[tid] = 0;
+        __syncthreads();
+    }
+
+    // ---- Y staging: clamped addresses and masks instead of branches, so that the loads are unconditional
+    YE yv[YU];
+    uint32_t ym[YU];
+    auto y_load = [&](int round) {
+#pragma unroll
+        for (int i = 0; i < YU; ++i) {
+            const int e = (round * YU + i) * NT + tid;
+            const int w = e & (SW - 1), t = e / SW;
+            const int n = t & (NS - 1), jb = t / NS;
+            const int slot = (W == 2 && YTER) ? (w & 63) * 2 + (w >> 6) : w;  // inverse of the layout rule
+            const int g = jb * SW + slot;
+            const bool ok = e < entries && y0 + n < rowsY && g < KW;
+            yv[i] = Yp[(int64_t)(ok ? y0 + n : y0) * KW + (ok ? g : 0)];
+            ym[i] = ok ? 0xffffffffu : 0u;
+        }
+    };
+    auto y_store = [&](int round) {
+#pragma unroll
+        for (int i = 0; i < YU; ++i) {
+            const int e = (round * YU + i) * NT + tid;
+            YE y = yv[i];
+            y.x &= ym[i];
+            y.y &= ym[i];
+            if constexpr (YTER) {
+                y.z &= ym[i];
+                y.w &= ym[i];
+            }
+            y = nz_neg(y);
+            if (e < entries) {
+                ylds[e] = y;
+                if constexpr (KIND == KIND_TBN_SV) {
+                    const int cnt = __builtin_popcount(y.x) + __builtin_popcount(y.y);
+                    if (cnt)
+                        atomicAdd(&ynnz[(e / SW) & (NS - 1)], cnt);
+                }
+            }
+        }
+    };
+
+    // ---- X stream of this wave: row groups gw, gw + GW, ... ; loads and multiplications keep their own positions
+    const int gw = blockIdx.x * WAVES + wave, GW = gridDim.x * WAVES;
+    const int my_iters = gw < groups ? (groups - gw + GW - 1) / GW : 0;
+    int lgroup = gw < groups ? gw : groups - 1, lj = 0;
+    const uint4 *lx[R];
+    auto set_rows = [&]() {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int row = lgroup * R + r;
+            row = row < rowsX ? row : rowsX - 1;
+            lx[r] = Xq + (int64_t)row * rstride;
+        }
+    };
+    set_rows();
+    uint4 ring[D][R];
+    auto issue = [&](int d) __attribute__((always_inline)) {
+        int idx = lj * 64 + lane;
+        if constexpr (!KFULL)
+            idx = idx < rstride ? idx : rstride - 1;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            ring[d][r] = lx[r][idx];
+        if (++lj == JWn) {
+            lj = 0;
+            lgroup += GW;
+            lgroup = lgroup < groups ? lgroup : groups - 1;
+            set_rows();
+        }
+    };
+
+    const int rounds = (entries + NT * YU - 1) / (NT * YU);
+    for (int round = 0; round + 1 < rounds; ++round) {
+        y_load(round);
+        y_store(round);
+    }
+    y_load(rounds - 1);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        issue(d);
+    y_store(rounds - 1);
+    __syncthreads();
+
+    int32_t acc[T::ACC][R][NS];
+    int32_t nnz[R];
+    auto clear = [&]() {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            nnz[r] = 0;
+#pragma unroll
+            for (int a = 0; a < T::ACC; ++a)
+#pragma unroll
+                for (int n = 0; n < NS; ++n)
+                    acc[a][r][n] = 0;
+        }
+    };
+    clear();
+    int cgroup = gw, cj = 0;
+
+    auto finish = [&]() __attribute__((always_inline)) {
+        int32_t val[V];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                if constexpr (KIND == KIND_BNN || KIND == KIND_TBN_SV)
+                    val[r * NS + n] = acc[0][r][n];
+                else if constexpr (KIND == KIND_TNN)
+                    val[r * NS + n] = acc[0][r][n] - 2 * acc[T::ACC - 1][r][n];
+                else
+                    val[r * NS + n] = nnz[r] - 2 * acc[0][r][n];
+            }
+        reduce_halving<V, 32>(val, lane);
+        constexpr int GROUP = 64 / V;
+        if ((lane % GROUP) == 0) {
+            const int idx = lane / GROUP;
+            const int r = idx / NS, n = idx % NS;
+            const int xr = cgroup * R + r, yn = y0 + n;
+            if (xr < rowsX && yn < rowsY) {
+                int32_t out = val[0];
+                if constexpr (KIND == KIND_BNN)
+                    out = K - 2 * out;
+                if constexpr (KIND == KIND_TBN_SV)
+                    out = ynnz[n] - 2 * out;
+                const int64_t at = TR ? (int64_t)yn * ldc + xr : (int64_t)xr * ldc + yn;
+                if (c16)
+                    reinterpret_cast<int16_t *>(C)[at] = (int16_t)out;  // K <= 32767 checked on the host
+                else
+                    C[at] = out;
+            }
+        }
+    };
+
+    // one step: take slot d of the ring, refill it at once (so that D loads stay in flight while this step is
+    // multiplied), multiply
+    auto consume = [&](int d, bool refill) __attribute__((always_inline)) {
+        uint4 xv[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            xv[r] = ring[d][r];
+        if (refill)
+            issue(d);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if constexpr (!KFULL) {
+                const uint32_t live = (cj * 64 + lane) < rstride ? 0xffffffffu : 0u;
+                xv[r].x &= live;
+                xv[r].y &= live;
+                xv[r].z &= live;
+                xv[r].w &= live;
+            }
+            if constexpr (!XBIN) {
+                xv[r] = nz_neg(xv[r]);
+                if constexpr (KIND == KIND_TBN) {
+                    popc_acc(nnz[r], xv[r].x);
+                    popc_acc(nnz[r], xv[r].y);
+                }
+            }
+        }
+        const YE *yb = ylds + (cj * NS) * SW;
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+            if constexpr (!XBIN) {
+                const YE y = yb[n * SW + lane];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    sk_mac<KIND>(acc[0][r][n], acc[T::ACC - 1][r][n], xv[r], y);
+            } else if constexpr (!YTER) {
+                // binary X, binary Y: the two words of the lane are adjacent in LDS
+                const uint4 yy = *reinterpret_cast<const uint4 *>(yb + n * SW + lane * 2);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    sk_mac<KIND>(acc[0][r][n], acc[0][r][n], make_uint2(xv[r].x, xv[r].y), make_uint2(yy.x, yy.y));
+                    sk_mac<KIND>(acc[0][r][n], acc[0][r][n], make_uint2(xv[r].z, xv[r].w), make_uint2(yy.z, yy.w));
+                }
+            } else {
+                const YE ya = yb[n * SW + lane], yc = yb[n * SW + 64 + lane];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    sk_mac<KIND>(acc[0][r][n], acc[0][r][n], make_uint2(xv[r].x, xv[r].y), ya);
+                    sk_mac<KIND>(acc[0][r][n], acc[0][r][n], make_uint2(xv[r].z, xv[r].w), yc);
+                }
+            }
+        }
+        if (++cj == JWn) {
+            finish();
+            clear();
+            cj = 0;
+            cgroup += GW;
+        }
+    };
+
+    // nsteps >= D for every wave that has work (the launcher picks D accordingly).  The steady loop refills
+    // unconditionally; the last D .. 2D-1 steps are peeled so that no load is issued beyond the wave's stream.
+    if (my_iters > 0) {
+        const int nsteps = my_iters * JWn;
+        const int nfull = (nsteps - D) / D;
+        for (int b = 0; b < nfull; ++b) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                consume(d, true);
+        }
+        const int rest = nsteps - D - nfull * D;  // steps not yet issued: 0 .. D-1
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            consume(d, d < rest);
+#pragma unroll
+        for (int d = 0; d < D - 1; ++d)
+            if (d < rest)
+                consume(d, false);
+    }
+}
+
+constexpr size_t kStreamMaxLds = 64 * 1024;  // per workgroup (static limit of a launch without opt-in)
+constexpr size_t kCuLds = 160 * 1024;
+constexpr int kComputeUnits = 256;
+
+// LDS bytes the streaming kernel needs for this problem, 0 if it cannot serve it (more than 8 short strings, a depth
+// whose strings do not fit in LDS, binary X strings of an odd number of words)
+template <int KIND> size_t stream_lds_bytes(const SkinnyArgs &a)
+{
+    using T = SkTraits<KIND>;
+    constexpr int W = sizeof(typename T::X) == 8 ? 2 : 1;
+    if (a.rowsY > 8 || (W == 2 && (a.KW & 1)))
+        return 0;
+    const int64_t JWn = (a.KW + 64 * W - 1) / (64 * W);
+    const int64_t bytes = JWn * 8 * 64 * W * (int64_t)sizeof(typename T::Y) + 8 * 4;
+    return bytes <= (int64_t)kStreamMaxLds ? (size_t)bytes : 0;
+}
+
+// How the streaming kernel is launched: rows per wave and step, workgroups (of 8 waves) per compute unit, and the
+// largest ring depth tried (the depth used is the largest of 8 / 4 / 2 / 1 within it that divides the steps per row).
+struct StreamShape {
+    int rows_per_wave, wg_per_cu, max_depth;
+};
+
+// workgroups of 8 waves in the grid: one per 8 row groups, at most wg_per_cu (and what fits in its LDS) per compute unit
+template <int KIND, int R> int stream_grid(const SkinnyArgs &a, size_t lds, int wg_per_cu)
+{
+    const int groups = (a.rowsX + R - 1) / R;
+    const int wgs = (groups + 7) / 8;
+    int per_cu = (int)(kCuLds / lds);
+    per_cu = per_cu < wg_per_cu ? per_cu : wg_per_cu;
+    const int maxwg = kComputeUnits * (per_cu < 1 ? 1 : per_cu);
+    return wgs < maxwg ? wgs : maxwg;
+}
+
+template <int KIND, int R, bool TR, bool KFULL, int D>
+hipError_t launch_stream_inst(const SkinnyArgs &a, size_t lds, int wg_per_cu)
+{
+    using T = SkTraits<KIND>;
+    constexpr int W = sizeof(typename T::X) == 8 ? 2 : 1, WAVES = 8, NS = 8;
+    const int JWn = (a.KW + 64 * W - 1) / (64 * W);
+    const int groups = (a.rowsX + R - 1) / R;
+    const int gx = stream_grid<KIND, R>(a, lds, wg_per_cu);
+    hipLaunchKernelGGL((gemm_skinny_stream_kernel<KIND, R, WAVES, TR, NS, KFULL, D>), dim3((unsigned)gx, 1),
+                       dim3(64 * WAVES), lds, a.stream, a.Xp, a.Yp, a.rowsX, a.rowsY, a.KW, a.K, a.C, a.ldc, a.c16, JWn,
+                       groups);
+    return hipGetLastError();
+}
+
+template <int KIND, int R, bool TR> hipError_t launch_stream_r(const SkinnyArgs &a, size_t lds, const StreamShape &sh)
+{
+    using T = SkTraits<KIND>;
+    constexpr int W = sizeof(typename T::X) == 8 ? 2 : 1;
+    const int JWn = (a.KW + 64 * W - 1) / (64 * W);
+    const bool full = a.KW % (64 * W) == 0;
+    // ring depth: at most what every working wave has in steps (whole rows of JWn steps, floor(groups / waves) of them
+    // or one), at most the shape's limit
+    const int groups = (a.rowsX + R - 1) / R;
+    const int64_t waves = (int64_t)stream_grid<KIND, R>(a, lds, sh.wg_per_cu) * 8;
+    const int64_t min_steps = (int64_t)JWn * (groups / waves > 1 ? groups / waves : 1);
+    int d = min_steps >= 8 ? 8 : min_steps >= 4 ? 4 : min_steps >= 2 ? 2 : 1;
+    d = d < sh.max_depth ? d : sh.max_depth;
+    if constexpr (R == 2)
+        d = d < 4 ? d : 4;  // two rows per step: a ring of 8 steps would not leave the registers for 8 waves per SIMD
+#define LB_STREAM_D(FULL)                                                                              \
+    (d == 8   ? launch_stream_inst<KIND, R, TR, FULL, (R == 2 ? 4 : 8)>(a, lds, sh.wg_per_cu)         \
+     : d == 4 ? launch_stream_inst<KIND, R, TR, FULL, 4>(a, lds, sh.wg_per_cu)                         \
+     : d == 2 ? launch_stream_inst<KIND, R, TR, FULL, 2>(a, lds, sh.wg_per_cu)                         \
+              : launch_stream_inst<KIND, R, TR, FULL, 1>(a, lds, sh.wg_per_cu))
+    return full ? LB_STREAM_D(true) : LB_STREAM_D(false);
+#undef LB_STREAM_D
+}
+
+template <int KIND> hipError_t launch_stream(const SkinnyArgs &a, bool tr, size_t lds, const StreamShape &sh)
+{
+    if (sh.rows_per_wave == 2)
+        return tr ? launch_stream_r<KIND, 2, true>(a, lds, sh) : launch_stream_r<KIND, 2, false>(a, lds, sh);
+    return tr ? launch_stream_r<KIND, 1, true>(a, lds, sh) : launch_stream_r<KIND, 1, false>(a, lds, sh);
+}
+
+// configurations 8 .. 13 of the benchmark hook force the streaming kernel in these shapes
+constexpr StreamShape kStreamForced[] = {{1, 2, 4}, {2, 2, 4}, {1, 4, 4}, {2, 4, 4}, {1, 2, 8}, {1, 4, 8}};
+constexpr int kChunkedConfigs = 8;
+constexpr int kStreamConfigs = (int)(sizeof(kStreamForced) / sizeof(kStreamForced[0]));
+
 template <int KIND, int R, int WAVES, bool TR, int NS = 8> hipError_t launch_sk(const SkinnyArgs &a)
 {
     const int64_t gx = ((int64_t)a.rowsX + WAVES * R - 1) / (WAVES * R);
@@ -272,6 +639,23 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
     // stream best with 2 rows per wave (binary operands, half the bytes per row: 4); a few thousand rows are
     // latency-bound and want many small waves in flight
     int cfg = g_skinny_forced.load(std::memory_order_relaxed);
+    // at most 8 short strings that fit in LDS whole: the streaming kernel (configurations 8 and up force it in a given
+    // shape; a problem it cannot serve falls back to the chunked kernel)
+    if (cfg < 0 || cfg >= kChunkedConfigs) {
+        const size_t lds = stream_lds_bytes<KIND>(a);
+        // Measured (cold operand, 4096 .. 131072 rows, depth 4096 .. 32768): the streaming kernel is 0-20 % faster than
+        // the chunked one except on the longest ternary-binary streams, which the chunked kernel already runs at the
+        // rate of a read-only kernel; two rows per wave pay from 32768 rows on (binary X: from 16384).
+        constexpr bool kTbn = KIND == KIND_TBN || KIND == KIND_TBN_SV;
+        const bool chunked_better = cfg < 0 && kTbn && a.rowsX >= 65536 && a.KW >= 256;
+        if (lds > 0 && !chunked_better) {
+            const int two_from = KIND == KIND_BNN ? 16384 : 32768;
+            const StreamShape sh = cfg >= kChunkedConfigs ? kStreamForced[cfg - kChunkedConfigs]
+                                                          : StreamShape{a.rowsX >= two_from ? 2 : 1, 4, 4};
+            return launch_stream<KIND>(a, tr, lds, sh);
+        }
+        cfg = -1;
+    }
     if (cfg < 0) {
         if (a.rowsX >= 16384)
             cfg = (KIND == KIND_BNN || KIND == KIND_TBN_SV) ? 7 : KIND == KIND_TNN ? 3 : 1;
@@ -315,7 +699,7 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
 
 }  // namespace
 
-int skinny_num_configs() { return 8; }
+int skinny_num_configs() { return kChunkedConfigs + kStreamConfigs; }
 void skinny_force_config(int cfg) { g_skinny_forced.store(cfg, std::memory_order_relaxed); }
 int skinny_forced_config() { return g_skinny_forced.load(std::memory_order_relaxed); }
 

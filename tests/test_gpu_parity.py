@@ -201,6 +201,33 @@ def test_gemm_skinny_every_configuration(kind):
         lb.lb_set_variant(3, -1)
 
 
+STREAM_SHAPES = [(9000, 8, 4096), (10000, 5, 8192), (5000, 8, 16384 + 128), (70000, 8, 2048), (33000, 3, 24576),
+                 (8, 9000, 4096), (3, 40000, 8192), (4100, 7, 64 * 77), (1, 8, 16384), (4097, 1, 32768),
+                 (600, 8, 65536), (2, 5000, 16384 + 70)]
+
+
+@pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
+def test_gemm_skinny_streaming_kernel(kind):
+    """The streaming depth-split kernel (short strings resident in LDS, waves walking over row groups with a ring of
+    loads in flight): one and two rows per wave, ring depths 1 / 2 / 4, depths that are and are not multiples of a
+    wave-wide step, more row groups than waves, both operand roles, odd word counts (binary strings then take the
+    chunked kernel), a padded ldc."""
+    try:
+        for cfg in (8, 9, -1):
+            lb.lb_set_variant(3, cfg)
+            for (M, N, K) in STREAM_SHAPES:
+                say(f"gemm_{kind} streaming skinny configuration {cfg} M={M} N={N} K={K}")
+                A, B = synth.make_custom(kind, M, N, K, seed=cfg * 10 + M + N + K)
+                ldc = N + 1
+                C = torch.full((M, ldc), -9, dtype=torch.int32, device="cuda")
+                run_gemm(kind, A, B, C=C, ldc=ldc)
+                got = C.cpu().numpy()
+                assert np.array_equal(got[:, :N], oracle.gemm(A, B)), (cfg, M, N, K)
+                assert np.all(got[:, N:] == -9)
+    finally:
+        lb.lb_set_variant(3, -1)
+
+
 @pytest.mark.parametrize("kind", ["bnn", "tnn", "tbn"])
 def test_gemm_depth_split(kind):
     """Few tiles and a long depth: the depth is split over workgroups whose partial products are added into a cleared
