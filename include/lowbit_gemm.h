@@ -240,6 +240,29 @@ LB_API int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_
                  int32_t *C, int64_t ldc, void *stream);
 
 /*
+ * Grouped launch of the 8-bit comparator: `count` independent products C_p = A_p B_p (the arguments of gemm_i8_mfma
+ * each) in ONE kernel launch, so that the paper's timing experiment -- many small matrices per algorithm (Section IV-B),
+ * ratios between algorithms (Table III) -- compares the packed kernels and the 8-bit comparator launch for launch.
+ * Same protocol as gemm_grouped: gemm_i8_grouped_table_bytes and gemm_i8_grouped_plan are HOST computations (the plan
+ * validates every problem as gemm_i8_mfma would and writes the launch table into caller-owned host memory);
+ * gemm_i8_grouped enqueues the launch on a 16-byte aligned DEVICE copy of that table.  Every problem is cut into
+ * 64 x 64 output tiles; operands of any alignment and leading dimension are accepted.  Output regions must not overlap.
+ */
+typedef struct lb_i8_problem {
+    int64_t M, N, K;
+    const int8_t *A;
+    int64_t lda;
+    const int8_t *B;
+    int64_t ldb;
+    int32_t *C;
+    int64_t ldc;
+} lb_i8_problem;
+LB_API size_t gemm_i8_grouped_table_bytes(int64_t count, const lb_i8_problem *problems);
+LB_API int gemm_i8_grouped_plan(int64_t count, const lb_i8_problem *problems, void *table, size_t table_bytes,
+                                int64_t *workgroups);
+LB_API int gemm_i8_grouped(int64_t count, const void *table_dev, int64_t workgroups, void *stream);
+
+/*
  * gemm_u8_mfma -- 8-bit linear-quantized product with zero points, the scheme of the paper's U8 baseline (eq. (2)
  * and (3), as in gemmlowp):  C[i][j] = sum_t (A[i][t] - zA) * (B[t][j] - zB)  with unsigned 8-bit A, B and integer
  * zero points 0 <= zA, zB <= 255, accumulated in int32.  Computed as eq. (3) prescribes: one matrix product on the

@@ -21,7 +21,7 @@ _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
            "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
-           "gemm_grouped_plan", "gemm_grouped", "gemm_grouped_static", "gemm_grouped_static_max_bytes", "gemm_requant", "gemm_i8_mfma", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
+           "gemm_grouped_plan", "gemm_grouped", "gemm_grouped_static", "gemm_grouped_static_max_bytes", "gemm_requant", "gemm_i8_mfma", "gemm_i8_grouped_table_bytes", "gemm_i8_grouped_plan", "gemm_i8_grouped", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_describe_plan", "lb_arch_supported", "lb_calib_sink_bytes", "lb_calib_clocks_bytes",
            "lb_calib_wall_clock_khz", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
 
@@ -30,6 +30,13 @@ class GemmProblem(ctypes.Structure):
     """lb_gemm_problem of the C header: one product of a grouped launch (device addresses as integers)."""
     _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("Ap", ctypes.c_void_p),
                 ("Bp", ctypes.c_void_p), ("C", ctypes.c_void_p), ("ldc", ctypes.c_int64)]
+
+
+class I8Problem(ctypes.Structure):
+    """lb_i8_problem of the C header: one product of a grouped launch of the 8-bit comparator."""
+    _fields_ = [("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("A", ctypes.c_void_p),
+                ("lda", ctypes.c_int64), ("B", ctypes.c_void_p), ("ldb", ctypes.c_int64), ("C", ctypes.c_void_p),
+                ("ldc", ctypes.c_int64)]
 
 
 class LowbitError(RuntimeError):
@@ -79,6 +86,12 @@ def lib() -> ctypes.CDLL:
         L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
         L.gemm_i8_mfma.restype = ci
         L.gemm_i8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
+        L.gemm_i8_grouped_table_bytes.restype = ctypes.c_size_t
+        L.gemm_i8_grouped_table_bytes.argtypes = [i64, vp]
+        L.gemm_i8_grouped_plan.restype = ci
+        L.gemm_i8_grouped_plan.argtypes = [i64, vp, vp, ctypes.c_size_t, ctypes.POINTER(i64)]
+        L.gemm_i8_grouped.restype = ci
+        L.gemm_i8_grouped.argtypes = [i64, vp, i64, vp]
         L.gemm_requant.restype = ci
         L.gemm_requant.argtypes = [ci, ci, i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.gemm_u8_mfma.restype = ci
@@ -269,6 +282,28 @@ def gemm_grouped_static(kind, count: int, table_host: Optional[torch.Tensor], wo
                                      _stream(stream)))
 
 
+def gemm_i8_grouped_table_bytes(problems: Sequence[I8Problem]) -> int:
+    return lib().gemm_i8_grouped_table_bytes(len(problems), (I8Problem * max(len(problems), 1))(*problems))
+
+
+def gemm_i8_grouped_plan(problems: Sequence[I8Problem]):
+    """Host-side planning: returns (table as a uint8 CPU tensor, workgroups)."""
+    arr = (I8Problem * max(len(problems), 1))(*problems)
+    nbytes = lib().gemm_i8_grouped_table_bytes(len(problems), arr)
+    wg = ctypes.c_int64(0)
+    if nbytes == 0:  # invalid problems: let the planning call report which rule they break
+        scratch = torch.zeros(16, dtype=torch.uint8)
+        _check(lib().gemm_i8_grouped_plan(len(problems), arr, scratch.data_ptr(), 16, ctypes.byref(wg)))
+        raise LowbitError(LB_EINVAL, "gemm_i8_grouped_table_bytes returned 0")
+    table = torch.zeros(nbytes, dtype=torch.uint8)
+    _check(lib().gemm_i8_grouped_plan(len(problems), arr, table.data_ptr(), nbytes, ctypes.byref(wg)))
+    return table, wg.value
+
+
+def gemm_i8_grouped(count: int, table_dev: Optional[torch.Tensor], workgroups: int, stream=None) -> None:
+    _check(lib().gemm_i8_grouped(count, _ptr(table_dev), workgroups, _stream(stream)))
+
+
 def gemm_requant(kind, out_planes: int, M, N, K, Ap, Bp, lo, hi=None, Out=None, stream=None):
     """Thresholded product written as N packed strings of depth M (1 = binary, 2 = ternary planes)."""
     if Out is None:
@@ -430,6 +465,27 @@ class GemmGroup:
     def run_static(self, stream=None):
         """The same launch through the entry point that keeps the table in the library's own device array."""
         gemm_grouped_static(self.kind, len(self.shapes), self.table_host, self.workgroups, stream)
+        return self.Cs
+
+
+class I8Group:
+    """A planned grouped launch of the 8-bit comparator over unpacked int8 operand pairs."""
+
+    def __init__(self, pairs, shapes, Cs=None):
+        """pairs: [(A, B)] int8 device tensors (M x K, K x N, row-major, any row stride); shapes: [(M, N, K)]."""
+        self.shapes, self.operands = list(shapes), list(pairs)
+        dev = self.operands[0][0].device if self.operands else torch.device("cuda")
+        self.Cs = list(Cs) if Cs is not None else [torch.empty((M, N), dtype=torch.int32, device=dev)
+                                                   for (M, N, K) in self.shapes]
+        probs = [I8Problem(M, N, K, _ptr(A) or None, A.stride(0) if A.dim() == 2 and A.numel() else max(K, 1),
+                           _ptr(B) or None, B.stride(0) if B.dim() == 2 and B.numel() else max(N, 1), _ptr(C) or None,
+                           C.stride(0) if C.dim() == 2 and C.numel() else max(N, 1))
+                 for (M, N, K), (A, B), C in zip(self.shapes, self.operands, self.Cs)]
+        table, self.workgroups = gemm_i8_grouped_plan(probs)
+        self.table_dev = table.to(dev)
+
+    def run(self, stream=None):
+        gemm_i8_grouped(len(self.shapes), self.table_dev, self.workgroups, stream)
         return self.Cs
 
 

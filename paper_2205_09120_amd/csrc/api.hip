@@ -380,6 +380,70 @@ int group_workgroups(int kind, const char *name, int64_t count, const lb_gemm_pr
     return LB_OK;
 }
 
+// Argument rules of gemm_i8_mfma, also applied to every problem of its grouped launch.
+int check_gemm_i8(const char *name, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
+                  int64_t ldb, const int32_t *C, int64_t ldc, bool *empty)
+{
+    *empty = false;
+    if (M < 0 || N < 0)
+        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
+    if (K <= 0)
+        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
+    // |a*b| <= 2^14, so the int32 sum is safe up to K = 2^17 - 1 for arbitrary int8 inputs
+    if (K > 131071)
+        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 131071 (int32 accumulation of int8 products)", name,
+                    (long long)K);
+    if (M > kMaxExtent || N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
+    if (M == 0 || N == 0) {
+        *empty = true;
+        return LB_OK;
+    }
+    if (!A || !B || !C)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    if (lda < K || ldb < N || ldc < N)
+        return fail(LB_EINVAL, "%s: lda=%lld ldb=%lld ldc=%lld too small", name, (long long)lda, (long long)ldb,
+                    (long long)ldc);
+    if (lda > INT64_MAX / M || ldb > INT64_MAX / K || ldc > INT64_MAX / M / 4)
+        return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
+    if (!aligned(C, 4))
+        return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    return LB_OK;
+}
+
+int i8_group_workgroups(const char *name, int64_t count, const lb_i8_problem *problems, int64_t *workgroups)
+{
+    if (count < 0 || (count > 0 && !problems))
+        return fail(LB_EINVAL, "%s: count=%lld with problems=%p", name, (long long)count, (const void *)problems);
+    if (count > 0x7fffffffLL)
+        return fail(LB_EOVERFLOW, "%s: count=%lld exceeds 2^31-1", name, (long long)count);
+    int64_t total = 0;
+    constexpr int T = lowbit::kI8GroupTile;
+    for (int64_t p = 0; p < count; ++p) {
+        const lb_i8_problem &q = problems[p];
+        bool empty;
+        char where[48];
+        snprintf(where, sizeof(where), "%s: problem %lld", name, (long long)p);
+        const int rc = check_gemm_i8(where, q.M, q.N, q.K, q.A, q.lda, q.B, q.ldb, q.C, q.ldc, &empty);
+        if (rc != LB_OK)
+            return rc;
+        if (empty)
+            continue;
+        total += ((q.M + T - 1) / T) * ((q.N + T - 1) / T);
+        if (total > 0x7fffffffLL)
+            return fail(LB_EOVERFLOW, "%s: more than 2^31-1 workgroups", name);
+    }
+    *workgroups = total;
+    return LB_OK;
+}
+
+size_t i8_group_table_bytes(int64_t count, int64_t workgroups)
+{
+    const size_t raw = sizeof(lowbit::I8GroupHeader) + (size_t)count * sizeof(lowbit::I8GroupRecord) +
+                       (size_t)workgroups * sizeof(uint32_t);
+    return (raw + 15) & ~(size_t)15;
+}
+
 size_t group_table_bytes(int64_t count, int64_t workgroups)
 {
     // header + records + one entry per workgroup, rounded up to 16 bytes
@@ -573,30 +637,94 @@ int gemm_i8_mfma(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, 
                  int32_t *C, int64_t ldc, void *stream)
 {
     const char *name = "gemm_i8_mfma";
-    if (M < 0 || N < 0)
-        return fail(LB_EINVAL, "%s: M=%lld N=%lld must be >= 0", name, (long long)M, (long long)N);
-    if (K <= 0)
-        return fail(LB_EINVAL, "%s: K=%lld must be >= 1", name, (long long)K);
-    // |a*b| <= 2^14, so the int32 sum is safe up to K = 2^17 - 1 for arbitrary int8 inputs
-    if (K > 131071)
-        return fail(LB_EOVERFLOW, "%s: K=%lld exceeds 131071 (int32 accumulation of int8 products)", name,
-                    (long long)K);
-    if (M > kMaxExtent || N > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: M=%lld N=%lld exceed 2^31-1", name, (long long)M, (long long)N);
-    if (M == 0 || N == 0)
-        return LB_OK;
-    if (!A || !B || !C)
-        return fail(LB_EINVAL, "%s: null pointer", name);
-    if (lda < K || ldb < N || ldc < N)
-        return fail(LB_EINVAL, "%s: lda=%lld ldb=%lld ldc=%lld too small", name, (long long)lda, (long long)ldb,
-                    (long long)ldc);
-    if (lda > INT64_MAX / M || ldb > INT64_MAX / K || ldc > INT64_MAX / M / 4)
-        return fail(LB_EOVERFLOW, "%s: matrix extent overflows", name);
-    if (!aligned(C, 4))
-        return fail(LB_EINVAL, "%s: C must be 4-byte aligned", name);
+    bool empty;
+    const int rc = check_gemm_i8(name, M, N, K, A, lda, B, ldb, C, ldc, &empty);
+    if (rc != LB_OK || empty)
+        return rc;
     if (const int rc_dev = check_device(name))
         return rc_dev;
     const hipError_t e = lowbit::launch_gemm_i8(M, N, K, A, lda, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+size_t gemm_i8_grouped_table_bytes(int64_t count, const lb_i8_problem *problems)
+{
+    int64_t wg = 0;
+    if (i8_group_workgroups("gemm_i8_grouped_table_bytes", count, problems, &wg) != LB_OK)
+        return 0;
+    return i8_group_table_bytes(count, wg);
+}
+
+int gemm_i8_grouped_plan(int64_t count, const lb_i8_problem *problems, void *table, size_t table_bytes,
+                         int64_t *workgroups)
+{
+    const char *name = "gemm_i8_grouped_plan";
+    if (!table || !workgroups)
+        return fail(LB_EINVAL, "%s: null pointer", name);
+    int64_t wg = 0;
+    const int rc = i8_group_workgroups(name, count, problems, &wg);
+    if (rc != LB_OK)
+        return rc;
+    const size_t need = i8_group_table_bytes(count, wg);
+    if (table_bytes < need)
+        return fail(LB_EINVAL, "%s: table_bytes=%zu < %zu", name, table_bytes, need);
+    memset(table, 0, need);
+    auto *hdr = static_cast<lowbit::I8GroupHeader *>(table);
+    auto *recs = reinterpret_cast<lowbit::I8GroupRecord *>(hdr + 1);
+    auto *owner = reinterpret_cast<uint32_t *>(recs + count);
+    hdr->magic = lowbit::kI8GroupMagic;
+    hdr->count = (uint32_t)count;
+    hdr->workgroups = (uint32_t)wg;
+    uint32_t next = 0;
+    constexpr int T = lowbit::kI8GroupTile;
+    for (int64_t p = 0; p < count; ++p) {
+        const lb_i8_problem &q = problems[p];
+        lowbit::I8GroupRecord &r = recs[p];
+        r.tile0 = next;
+        if (q.M == 0 || q.N == 0)
+            continue;  // owns no workgroup; the zeroed record is never read
+        r.A = q.A;
+        r.B = q.B;
+        r.C = q.C;
+        r.lda = q.lda;
+        r.ldb = q.ldb;
+        r.ldc = q.ldc;
+        r.M = (int32_t)q.M;
+        r.N = (int32_t)q.N;
+        r.K = (int32_t)q.K;
+        r.nMB = (int32_t)((q.M + T - 1) / T);
+        r.mode = lowbit::i8_fetch_mode(q.M, q.N, q.K, q.A, q.lda, q.B, q.ldb, T, T);
+        const uint32_t tiles = (uint32_t)r.nMB * (uint32_t)((q.N + T - 1) / T);
+        for (uint32_t t = 0; t < tiles; ++t)
+            owner[next + t] = (uint32_t)p;
+        next += tiles;
+    }
+    *workgroups = wg;
+    return LB_OK;
+}
+
+int gemm_i8_grouped(int64_t count, const void *table_dev, int64_t workgroups, void *stream)
+{
+    const char *name = "gemm_i8_grouped";
+    if (count < 0 || workgroups < 0)
+        return fail(LB_EINVAL, "%s: count=%lld workgroups=%lld must be >= 0", name, (long long)count,
+                    (long long)workgroups);
+    if (count > 0x7fffffffLL || workgroups > 0x7fffffffLL)
+        return fail(LB_EOVERFLOW, "%s: count=%lld workgroups=%lld exceed 2^31-1", name, (long long)count,
+                    (long long)workgroups);
+    if (workgroups == 0)
+        return LB_OK;
+    if (count == 0)
+        return fail(LB_EINVAL, "%s: %lld workgroups for no problems", name, (long long)workgroups);
+    if (!table_dev || !aligned(table_dev, 16))
+        return fail(LB_EINVAL, "%s: table_dev must be a 16-byte aligned device pointer", name);
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
+    const hipError_t e = lowbit::launch_gemm_i8_group(static_cast<const lowbit::I8GroupHeader *>(table_dev),
+                                                      (uint32_t)count, (uint32_t)workgroups,
+                                                      static_cast<hipStream_t>(stream));
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;

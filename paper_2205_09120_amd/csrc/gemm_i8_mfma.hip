@@ -63,10 +63,18 @@ __device__ __forceinline__ void transpose4x4(const uint32_t r[4], uint32_t o[4])
 // bytes directly issues at a fraction of that rate and slowed the whole kernel down by a factor of two)
 __device__ __forceinline__ uint32_t bytesum(uint32_t x, uint32_t c) { return __builtin_amdgcn_sad_u8(x, 0u, c); }
 
+// LDS bytes of one of the two staging buffers of a 64*TM x 64*TN tile
+template <int TM, int TN> struct I8TileLds {
+    static constexpr int A_BYTES = 64 * TM * A_STRIDE;
+    static constexpr int B_BYTES = 4 * 4 * ((64 * TN / 4) * 16 + 64);
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+};
+
+// One workgroup tile (block row mb, block column nb) of C = A B; smem_base: two staging buffers of I8TileLds::STAGE bytes.
 template <int TM, int TN, int MODE, bool U8>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_mfma_kernel(
-    int M, int N, int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
-    int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
+__device__ __forceinline__ void gemm_i8_tile(int M, int N, int K, const int8_t *__restrict__ A, int64_t lda,
+                                             const int8_t *__restrict__ B, int64_t ldb, int32_t *__restrict__ C,
+                                             int64_t ldc, int mb, int nb, int zA, int zB, uint8_t *smem_base)
 {
     constexpr uint32_t FLIP = U8 ? 0x80808080u : 0u;  // unsigned byte -> signed byte minus 128
     constexpr int BM = 64 * TM, BN = 64 * TN;
@@ -77,14 +85,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
     constexpr int A_PT = BM * 4 / 256;               // uint4 loads of A per thread
     constexpr int B_UNITS = 4 * NQ;                  // (depth block, column quad) units
     constexpr int B_PT = (B_UNITS + 255) / 256;
+    static_assert(A_BYTES == I8TileLds<TM, TN>::A_BYTES && B_BYTES == I8TileLds<TM, TN>::B_BYTES, "LDS layout");
 
-    __shared__ __attribute__((aligned(16))) uint8_t smem[2][A_BYTES + B_BYTES];
-
-    const int bid = blockIdx.x;
-    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
-    if ((bid >> 3) >= tiles_per_xcd || idx >= nMB * nNB)
-        return;
-    const int nb = idx / nMB, mb = idx - nb * nMB;  // the M blocks of one N block are adjacent: they share the B tile
+    uint8_t(*smem)[A_BYTES + B_BYTES] = reinterpret_cast<uint8_t(*)[A_BYTES + B_BYTES]>(smem_base);
     const int m0 = mb * BM, n0 = nb * BN;
 
     const int tid = threadIdx.x;
@@ -404,6 +407,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) voi
                     C[(int64_t)row * ldc + col] = out;
             }
         }
+}
+
+template <int TM, int TN, int MODE, bool U8>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_mfma_kernel(
+    int M, int N, int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
+    int32_t *__restrict__ C, int64_t ldc, int nMB, int nNB, int tiles_per_xcd, int zA, int zB)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * I8TileLds<TM, TN>::STAGE];
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nMB * nNB)
+        return;
+    const int nb = idx / nMB, mb = idx - nb * nMB;  // the M blocks of one N block are adjacent: they share the B tile
+    gemm_i8_tile<TM, TN, MODE, U8>(M, N, K, A, lda, B, ldb, C, ldc, mb, nb, zA, zB, smem);
+}
+
+// Grouped launch of the comparator: `count` independent products in one grid of 64 x 64 tiles.  The table (built on
+// the host) maps each workgroup id to a problem record; the record carries the fetch mode the single-product launcher
+// would pick for that problem.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2))) void gemm_i8_group_kernel(
+    const I8GroupHeader *__restrict__ table, uint32_t count)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * I8TileLds<1, 1>::STAGE];
+    const uint32_t bid = blockIdx.x;
+    if (table->magic != kI8GroupMagic || table->count != count || table->workgroups != gridDim.x)
+        return;
+    const I8GroupRecord *__restrict__ recs = reinterpret_cast<const I8GroupRecord *>(table + 1);
+    const uint32_t *__restrict__ owner = reinterpret_cast<const uint32_t *>(recs + count);
+    const uint32_t p = owner[bid];
+    if (p >= count)
+        return;
+    const I8GroupRecord r = recs[p];
+    const int local = (int)(bid - r.tile0);
+    const int nb = local / r.nMB, mb = local - nb * r.nMB;
+    switch (r.mode) {
+    case 0: gemm_i8_tile<1, 1, 0, false>(r.M, r.N, r.K, r.A, r.lda, r.B, r.ldb, r.C, r.ldc, mb, nb, 0, 0, smem); break;
+    case 1: gemm_i8_tile<1, 1, 1, false>(r.M, r.N, r.K, r.A, r.lda, r.B, r.ldb, r.C, r.ldc, mb, nb, 0, 0, smem); break;
+    case 2: gemm_i8_tile<1, 1, 2, false>(r.M, r.N, r.K, r.A, r.lda, r.B, r.ldb, r.C, r.ldc, mb, nb, 0, 0, smem); break;
+    default: gemm_i8_tile<1, 1, 3, false>(r.M, r.N, r.K, r.A, r.lda, r.B, r.ldb, r.C, r.ldc, mb, nb, 0, 0, smem); break;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -1001,6 +1044,26 @@ __global__ __launch_bounds__(512) void gemm_i8_dl_kernel(int M, int N, int K, co
         }
 }
 
+}  // namespace
+
+// How the 4-wave kernel fetches a problem with BM x BN tiles (see the fetch modes in gemm_i8_tile)
+int i8_fetch_mode(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, int BM, int BN)
+{
+    const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
+                         (reinterpret_cast<uintptr_t>(B) % 4 == 0) && (ldb % 4 == 0);
+    const bool whole = (M % BM) == 0 && (N % BN) == 0 && (K % BK) == 0;
+    const bool can_clamp = (N % 4) == 0 && (K % 16) == 0 && N >= 4 && K >= 16;
+    return (aligned && whole) ? 0 : (aligned && can_clamp) ? 1 : (N >= 4 && K >= BK) ? 2 : 3;
+}
+
+hipError_t launch_gemm_i8_group(const I8GroupHeader *table_dev, uint32_t count, uint32_t workgroups, hipStream_t stream)
+{
+    hipLaunchKernelGGL(gemm_i8_group_kernel, dim3(workgroups), dim3(256), 0, stream, table_dev, count);
+    return hipGetLastError();
+}
+
+namespace {
+
 template <int TM, int TN, bool U8>
 hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                        int32_t *C, int64_t ldc, hipStream_t stream, int zA, int zB)
@@ -1012,18 +1075,15 @@ hipError_t launch_tile(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t
     const int64_t grid = (int64_t)tiles_per_xcd * 8;
     if (grid > 0x7fffffffLL)
         return hipErrorInvalidConfiguration;
-    const bool aligned = (reinterpret_cast<uintptr_t>(A) % 16 == 0) && (lda % 16 == 0) &&
-                         (reinterpret_cast<uintptr_t>(B) % 4 == 0) && (ldb % 4 == 0);
-    const bool whole = (M % BM) == 0 && (N % BN) == 0 && (K % BK) == 0;
-    const bool can_clamp = (N % 4) == 0 && (K % 16) == 0 && N >= 4 && K >= 16;
+    const int mode = i8_fetch_mode(M, N, K, A, lda, B, ldb, BM, BN);
     const dim3 g((unsigned)grid), b(256);
-    if (aligned && whole)
+    if (mode == 0)
         hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 0, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
                            ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
-    else if (aligned && can_clamp)
+    else if (mode == 1)
         hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 1, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
                            ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
-    else if (N >= 4 && K >= BK)
+    else if (mode == 2)
         hipLaunchKernelGGL((gemm_i8_mfma_kernel<TM, TN, 2, U8>), g, b, 0, stream, (int)M, (int)N, (int)K, A, lda, B,
                            ldb, C, ldc, nMB, nNB, tiles_per_xcd, zA, zB);
     else

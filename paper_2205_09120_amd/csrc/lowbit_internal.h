@@ -132,6 +132,27 @@ hipError_t launch_gemm_u8(int64_t M, int64_t N, int64_t K, const uint8_t *A, int
                           int zA, int zB, int32_t *C, int64_t ldc, hipStream_t stream);
 hipError_t launch_gemm_i8_skinny(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
                                  int64_t ldb, int32_t *C, int64_t ldc, hipStream_t stream);
+// Grouped launch of the comparator: 64 x 64 tiles (the instance small products take), table = header, `count` records,
+// one uint32 per workgroup naming its record; built on the host (api.hip), copied to the device by the caller.
+constexpr int kI8GroupTile = 64;
+constexpr uint32_t kI8GroupMagic = 0x4c423847u;  // "LB8G"
+struct I8GroupHeader {
+    uint32_t magic, count, workgroups, reserved;
+};
+struct I8GroupRecord {
+    const int8_t *A;
+    const int8_t *B;
+    int32_t *C;
+    int64_t lda, ldb, ldc;
+    int32_t M, N, K;
+    int32_t nMB;     // tiles along M; tile t of the problem is (nb, mb) = (t / nMB, t % nMB)
+    uint32_t tile0;  // first workgroup of the problem
+    int32_t mode;    // fetch mode (i8_fetch_mode)
+    int32_t reserved[2];
+};
+static_assert(sizeof(I8GroupHeader) == 16 && sizeof(I8GroupRecord) == 80, "table layout is part of the host/device contract");
+int i8_fetch_mode(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, int BM, int BN);
+hipError_t launch_gemm_i8_group(const I8GroupHeader *table_dev, uint32_t count, uint32_t workgroups, hipStream_t stream);
 void i8_force_tile(int t);  // -1 = shape-based, 0 = 128x128, 1 = 256x256, 2 = 256x128 (4 waves each),
                             // 3 / 4 / 5 = wave-specialised 256x128 with 3 / 2 / 4 depth steps of prefetch,
                             // 6 = direct-to-LDS 256x128 with 4 stages of 64 depth bytes, 7 / 8 / 9 = direct-to-LDS

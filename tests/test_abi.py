@@ -351,3 +351,34 @@ def test_arch_check_is_host_logic(L):
     for other in ("gfx942", "gfx942:sramecc+:xnack-", "gfx90a", "gfx9500", "gfx95", "", "sm_90"):
         assert not binding.lb_arch_supported(other), other
     assert L.lb_arch_supported(None) == 0
+
+
+def test_i8_grouped_planning_and_validation(L):
+    """The grouped launch of the 8-bit comparator plans on the host: table structure and argument rules, no GPU."""
+    import numpy as np
+    P = binding.I8Problem
+    probs = [P(72, 24, 128, 0x10000, 128, 0x20000, 24, 0x30000, 24),      # 2 x 1 tiles, N not a multiple of 16
+             P(0, 9, 64, None, 64, None, 9, None, 9),                     # empty: owns no workgroup
+             P(130, 70, 191, 0x40001, 191, 0x50003, 70, 0x60000, 75)]     # unaligned operands, ragged: 3 x 2 tiles
+    table, wg = binding.gemm_i8_grouped_plan(probs)
+    assert wg == 2 + 0 + 6
+    assert table.numel() == binding.gemm_i8_grouped_table_bytes(probs) == (16 + 3 * 80 + 8 * 4 + 15) // 16 * 16
+    t = table.numpy()
+    hdr = t[:16].view(np.uint32)
+    assert hdr[0] == 0x4c423847 and hdr[1] == 3 and hdr[2] == 8
+    owner = t[16 + 3 * 80: 16 + 3 * 80 + 8 * 4].view(np.uint32)
+    assert owner.tolist() == [0, 0, 2, 2, 2, 2, 2, 2]
+    rec2 = t[16 + 2 * 80: 16 + 3 * 80]
+    assert rec2[:8].view(np.uint64)[0] == 0x40001 and rec2[48:60].view(np.int32).tolist() == [130, 70, 191]
+    assert rec2[60:64].view(np.int32)[0] == 3 and rec2[64:68].view(np.uint32)[0] == 2     # tiles along M, first workgroup
+    assert rec2[68:72].view(np.int32)[0] == 2                     # unaligned, K >= 64, N >= 4: the overlap fetch
+    assert t[16:16 + 80][68:72].view(np.int32)[0] == 1            # aligned, N % 4 == 0, K % 16 == 0: clamped fetch
+    bad = P(8, 8, 64, 0x1000, 32, 0x2000, 8, 0x3000, 8)           # lda < K
+    assert binding.gemm_i8_grouped_table_bytes([probs[0], bad]) == 0 and b"problem 1" in L.lb_last_error()
+    with pytest.raises(binding.LowbitError):
+        binding.gemm_i8_grouped_plan([P(8, 8, 2 ** 17, 0x1000, 2 ** 17, 0x2000, 8, 0x3000, 8)])
+    assert L.gemm_i8_grouped(0, None, 0, None) == binding.LB_OK
+    assert L.gemm_i8_grouped(1, None, 1, None) == binding.LB_EINVAL
+    assert L.gemm_i8_grouped(1, 0x1004, 1, None) == binding.LB_EINVAL
+    assert L.gemm_i8_grouped(0, 0x1000, 1, None) == binding.LB_EINVAL
+    assert L.gemm_i8_grouped(1, 0x1000, 2 ** 31, None) == binding.LB_EOVERFLOW

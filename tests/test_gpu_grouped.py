@@ -103,3 +103,75 @@ def test_grouped_empty_group_and_mismatched_table():
     torch.cuda.synchronize()
     for (A, B), C in zip(mats, Cs):
         assert np.array_equal(C.cpu().numpy(), oracle.gemm(A, B))
+
+
+# ------------------------------------------------------------------ grouped launch of the 8-bit comparator
+
+def build_i8_group(shapes, seed0, ldc_extra=0, misalign=False):
+    rng = np.random.default_rng(seed0)
+    mats, pairs, Cs = [], [], []
+    for (M, N, K) in shapes:
+        A = rng.integers(-128, 128, (M, K), dtype=np.int8)
+        B = rng.integers(-128, 128, (K, N), dtype=np.int8)
+        mats.append((A, B))
+        if misalign and M and N:
+            # operands at odd addresses with odd leading dimensions: views into larger buffers
+            bufA = torch.zeros(M * (K + 3) + 1, dtype=torch.int8, device="cuda")
+            dA = bufA[1:].view(M, K + 3)[:, :K]
+            dA.copy_(torch.from_numpy(A))
+            bufB = torch.zeros(K * (N + 1) + 3, dtype=torch.int8, device="cuda")
+            dB = bufB[3:].view(K, N + 1)[:, :N]
+            dB.copy_(torch.from_numpy(B))
+        else:
+            dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+        pairs.append((dA, dB))
+        Cs.append(torch.full((M, N + ldc_extra), -777, dtype=torch.int32, device="cuda"))
+    return mats, pairs, Cs
+
+
+def test_i8_grouped_paper_shape_grid():
+    shapes = list(synth.paper_shape_grid())
+    say("gemm_i8_grouped: the 64 shapes of the paper's grid in one launch")
+    mats, pairs, Cs = build_i8_group(shapes, 7000)
+    g = lb.I8Group(pairs, shapes, Cs)
+    g.run()
+    torch.cuda.synchronize()
+    for (A, B), C, shp in zip(mats, Cs, shapes):
+        assert np.array_equal(C.cpu().numpy(), oracle.gemm(A, B)), shp
+
+
+I8_RAGGED = [(1, 1, 1), (64, 64, 64), (65, 67, 66), (3, 200, 63), (200, 3, 129), (64, 64, 4096), (0, 9, 64), (9, 0, 64),
+             (33, 47, 1000), (130, 70, 191), (128, 128, 131071), (257, 2, 64), (2, 257, 640), (100, 16, 48), (72, 24, 128)]
+
+
+@pytest.mark.parametrize("misalign", [False, True])
+def test_i8_grouped_ragged_empty_ldc_and_alignment(misalign):
+    say(f"gemm_i8_grouped: ragged / empty problems, every fetch mode in one grid, ldc > N, misaligned={misalign}")
+    mats, pairs, Cs = build_i8_group(I8_RAGGED, 7100, ldc_extra=3, misalign=misalign)
+    g = lb.I8Group(pairs, I8_RAGGED, Cs)
+    g.run()
+    g.run()
+    torch.cuda.synchronize()
+    for (A, B), C, (M, N, K) in zip(mats, Cs, I8_RAGGED):
+        got = C.cpu().numpy()
+        if M == 0 or N == 0:
+            assert np.all(got == -777)
+            continue
+        assert np.array_equal(got[:, :N], oracle.gemm(A, B)), (M, N, K)
+        assert np.all(got[:, N:] == -777), (M, N, K)
+
+
+def test_i8_grouped_mismatched_table_is_refused():
+    say("gemm_i8_grouped: a table planned for another count or grid is refused by the kernel")
+    shapes = [(20, 30, 100), (40, 10, 64)]
+    mats, pairs, Cs = build_i8_group(shapes, 7200)
+    g = lb.I8Group(pairs, shapes, Cs)
+    lb.gemm_i8_grouped(3, g.table_dev, g.workgroups)
+    lb.gemm_i8_grouped(2, g.table_dev, g.workgroups + 1)
+    torch.cuda.synchronize()
+    for C in Cs:
+        assert torch.all(C == -777)
+    g.run()
+    torch.cuda.synchronize()
+    for (A, B), C in zip(mats, Cs):
+        assert np.array_equal(C.cpu().numpy(), oracle.gemm(A, B))
