@@ -103,7 +103,7 @@ LB_API int pack_ternary(const int8_t *src, int64_t rows, int64_t K, int64_t stri
  *             pack_binary / pack_ternary(fmap, rows = batch*H*W, K = C, stride_r = C, stride_k = 1).
  *   planes    1 = binary strings, 2 = ternary strings (plus and minus word adjacent).
  *   C         channels; must be a multiple of 64 (LB_EUNSUPPORTED otherwise: unroll the int8 map and use pack_*).
- *   kh, kw    window; stride_h/w >= 1; pad_h/w >= 0 (zero padding).
+ *   kh, kw    window; stride_h/w >= 1; pad_h/w >= 0 (padding with zero WORDS, see Bp).
  *   Bp        device, out: N = batch*OH*OW bit strings of depth K = kh*kw*C with OH = (H + 2*pad_h - kh)/stride_h + 1,
  *             OW likewise; string n = (b*OH + oy)*OW + ox; depth index (ky*kw + kx)*C + c.  Size
  *             packed_binary_bytes(N, K) or packed_ternary_bytes(N, K).  Positions in the padding are zero words:
@@ -113,6 +113,24 @@ LB_API int pack_ternary(const int8_t *src, int64_t rows, int64_t K, int64_t stri
  */
 LB_API int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int64_t W, int64_t C, int kh, int kw,
                          int stride_h, int stride_w, int pad_h, int pad_w, uint64_t *Bp, void *stream);
+
+/*
+ * conv_gemm -- a convolution layer as one call: C = A * im2col(feature map), with the unrolled operand never written.
+ * The product kernel gathers the packed words of the right operand (depth order (ky, kx, c), eq. (5)) from the
+ * channel-packed feature map while it stages its tiles; the values written are those of im2col_packed followed by
+ * gemm_bnn / gemm_tnn.
+ *
+ *   kind      0 = BNN (binary filters, binary map), 1 = TNN (ternary filters, ternary map).  2 (TBN) is
+ *             LB_EUNSUPPORTED: that kernel keeps the binary operand in scalar registers; use im2col_packed + gemm_tbn.
+ *   Ap        device, packed filters: M strings of depth K = kh*kw*C in (ky, kx, c) order
+ *   Fp        device, packed feature map as for im2col_packed (batch*H*W strings of depth C, C a multiple of 64)
+ *   C         device, int32 row-major M x N with N = batch*OH*OW (string n = (b*OH + oy)*OW + ox), ldc >= N; overwritten
+ *   padding   positions outside the map contribute zero words: the ternary value 0, or the binary value +1
+ * Geometry rules and errors as for im2col_packed and gemm_*; an empty problem is a valid no-op.
+ */
+LB_API int conv_gemm(int kind, int64_t M, const uint64_t *Ap, const uint64_t *Fp, int64_t batch, int64_t H, int64_t W,
+                     int64_t C, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int32_t *Cout,
+                     int64_t ldc, void *stream);
 
 /*
  * gemm_bnn -- binary x binary, eq. (6):  C[i][j] = K - 2 * sum_w popcount(Ap[i][w] xor Bp[j][w]).

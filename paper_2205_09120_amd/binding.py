@@ -20,7 +20,7 @@ OP_BNN, OP_TNN, OP_TBN = 0, 1, 2
 _OPS = {"bnn": OP_BNN, "tnn": OP_TNN, "tbn": OP_TBN}
 
 EXPORTS = ("lb_last_error", "lb_format_version", "packed_binary_bytes", "packed_ternary_bytes", "pack_binary",
-           "pack_ternary", "im2col_packed", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
+           "pack_ternary", "im2col_packed", "conv_gemm", "gemm_bnn", "gemm_tnn", "gemm_tbn", "gemm_c16", "gemm_grouped_table_bytes",
            "gemm_grouped_plan", "gemm_grouped", "gemm_grouped_static", "gemm_grouped_static_max_bytes", "gemm_requant", "gemm_i8_mfma", "gemm_i8_grouped_table_bytes", "gemm_i8_grouped_plan", "gemm_i8_grouped", "gemm_u8_mfma", "packed_u4_bytes", "pack_u4", "gemm_u4_mfma", "packed_t4_bytes", "pack_t4", "gemm_t4_mfma", "lb_set_variant", "lb_num_variants",
            "lb_variant_name", "lb_describe_plan", "lb_arch_supported", "lb_calib_sink_bytes", "lb_calib_clocks_bytes",
            "lb_calib_wall_clock_khz", "lb_calib_valu_lane_instr", "lb_calib_valu", "lb_calib_stream")
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.gemm_grouped_static.argtypes = [ci, i64, vp, ctypes.c_size_t, i64, vp]
         L.im2col_packed.restype = ci
         L.im2col_packed.argtypes = [vp, ci, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, vp]
+        L.conv_gemm.restype = ci
+        L.conv_gemm.argtypes = [ci, i64, vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.gemm_i8_mfma.restype = ci
         L.gemm_i8_mfma.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64, vp]
         L.gemm_i8_grouped_table_bytes.restype = ctypes.c_size_t
@@ -196,6 +198,23 @@ def im2col_packed(Fp: torch.Tensor, planes: int, batch: int, H: int, W: int, C: 
     _check(lib().im2col_packed(_ptr(Fp), planes, batch, H, W, C, kh, kw, stride_h, stride_w, pad_h, pad_w, _ptr(Bp),
                                _stream(stream)))
     return Bp
+
+
+def conv_gemm(kind, M: int, Ap: torch.Tensor, Fp: torch.Tensor, batch: int, H: int, W: int, C: int, kh: int, kw: int,
+              stride_h: int = 1, stride_w: int = 1, pad_h: int = 0, pad_w: int = 0, Cout: Optional[torch.Tensor] = None,
+              ldc: Optional[int] = None, stream=None) -> torch.Tensor:
+    """Convolution as an implicit product: (M filters) x (batch*OH*OW output pixels), int32, row-major."""
+    OH = (H + 2 * pad_h - kh) // stride_h + 1 if H + 2 * pad_h >= kh else 0
+    OW = (W + 2 * pad_w - kw) // stride_w + 1 if W + 2 * pad_w >= kw else 0
+    N = batch * OH * OW
+    if Cout is None:
+        Cout = torch.empty((M, N), dtype=torch.int32, device=Fp.device if Fp is not None else "cuda")
+        ldc = max(N, 1)
+    elif ldc is None:
+        ldc = Cout.stride(0) if Cout.dim() == 2 else N
+    _check(lib().conv_gemm(_OPS.get(kind, kind), M, _ptr(Ap), _ptr(Fp), batch, H, W, C, kh, kw, stride_h, stride_w,
+                           pad_h, pad_w, _ptr(Cout), ldc, _stream(stream)))
+    return Cout
 
 
 def _gemm(fn, M, N, K, Ap, Bp, C, ldc, stream):

@@ -444,6 +444,48 @@ size_t i8_group_table_bytes(int64_t count, int64_t workgroups)
     return (raw + 15) & ~(size_t)15;
 }
 
+// Geometry rules shared by im2col_packed and conv_gemm; fills *g.  *empty: nothing to compute (batch == 0 or a window
+// larger than the padded map).
+int check_conv_geom(const char *name, int64_t batch, int64_t H, int64_t W, int64_t C, int kh, int kw, int stride_h,
+                    int stride_w, int pad_h, int pad_w, lowbit::Im2colGeom *g, bool *empty)
+{
+    *empty = false;
+    if (batch < 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0)
+        return fail(LB_EINVAL, "%s: bad geometry batch=%lld H=%lld W=%lld C=%lld window %dx%d stride %dx%d pad %dx%d",
+                    name, (long long)batch, (long long)H, (long long)W, (long long)C, kh, kw, stride_h, stride_w, pad_h,
+                    pad_w);
+    if (C % 64 != 0)
+        return fail(LB_EUNSUPPORTED, "%s: C=%lld is not a multiple of 64", name, (long long)C);
+    constexpr int64_t kLim = 1 << 24;  // keeps every product below in 64 bits and the map extents in 32
+    if (H > kLim || W > kLim || C > kLim * 64 || kh > 4096 || kw > 4096 || stride_h > kLim || stride_w > kLim ||
+        pad_h > kLim || pad_w > kLim || batch > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: geometry too large", name);
+    const int64_t OH = (H + 2 * pad_h - kh) >= 0 ? (H + 2 * pad_h - kh) / stride_h + 1 : 0;
+    const int64_t OW = (W + 2 * pad_w - kw) >= 0 ? (W + 2 * pad_w - kw) / stride_w + 1 : 0;
+    if (batch == 0 || OH == 0 || OW == 0) {
+        *empty = true;
+        return LB_OK;
+    }
+    const int64_t CW = C / 64;
+    const int64_t kwout = (int64_t)kh * kw * CW;
+    if (kwout > kMaxExtent / 64 || OH * OW > kMaxExtent || batch > INT64_MAX / (OH * OW) / kwout / 16)
+        return fail(LB_EOVERFLOW, "%s: packed operand too large", name);
+    g->batch = batch;
+    g->H = (int)H;
+    g->W = (int)W;
+    g->CW = (int)CW;
+    g->OH = (int)OH;
+    g->OW = (int)OW;
+    g->kh = kh;
+    g->kw = kw;
+    g->sh = stride_h;
+    g->sw = stride_w;
+    g->ph = pad_h;
+    g->pw = pad_w;
+    return LB_OK;
+}
+
 size_t group_table_bytes(int64_t count, int64_t workgroups)
 {
     // header + records + one entry per workgroup, rounded up to 16 bytes
@@ -823,45 +865,67 @@ int im2col_packed(const uint64_t *Fp, int planes, int64_t batch, int64_t H, int6
     const char *name = "im2col_packed";
     if (planes != 1 && planes != 2)
         return fail(LB_EINVAL, "%s: planes=%d must be 1 (binary) or 2 (ternary)", name, planes);
-    if (batch < 0 || H <= 0 || W <= 0 || C <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
-        pad_w < 0)
-        return fail(LB_EINVAL, "%s: bad geometry batch=%lld H=%lld W=%lld C=%lld window %dx%d stride %dx%d pad %dx%d",
-                    name, (long long)batch, (long long)H, (long long)W, (long long)C, kh, kw, stride_h, stride_w, pad_h,
-                    pad_w);
-    if (C % 64 != 0)
-        return fail(LB_EUNSUPPORTED, "%s: C=%lld is not a multiple of 64", name, (long long)C);
-    constexpr int64_t kLim = 1 << 24;  // keeps every product below in 64 bits and the map extents in 32
-    if (H > kLim || W > kLim || C > kLim * 64 || kh > 4096 || kw > 4096 || stride_h > kLim || stride_w > kLim ||
-        pad_h > kLim || pad_w > kLim || batch > kMaxExtent)
-        return fail(LB_EOVERFLOW, "%s: geometry too large", name);
-    const int64_t OH = (H + 2 * pad_h - kh) >= 0 ? (H + 2 * pad_h - kh) / stride_h + 1 : 0;
-    const int64_t OW = (W + 2 * pad_w - kw) >= 0 ? (W + 2 * pad_w - kw) / stride_w + 1 : 0;
-    if (batch == 0 || OH == 0 || OW == 0)
-        return LB_OK;
-    const int64_t CW = C / 64;
-    const int64_t kwout = (int64_t)kh * kw * CW;
-    if (kwout > kMaxExtent || OH * OW > kMaxExtent || batch > INT64_MAX / (OH * OW) / kwout / 16)
-        return fail(LB_EOVERFLOW, "%s: packed operand too large", name);
+    lowbit::Im2colGeom g;
+    bool empty;
+    const int rc = check_conv_geom(name, batch, H, W, C, kh, kw, stride_h, stride_w, pad_h, pad_w, &g, &empty);
+    if (rc != LB_OK || empty)
+        return rc;
     if (!Fp || !Bp)
         return fail(LB_EINVAL, "%s: null pointer", name);
     if (!aligned(Fp, 16) || !aligned(Bp, 16))
         return fail(LB_EINVAL, "%s: operands must be 16-byte aligned", name);
-    lowbit::Im2colGeom g;
-    g.batch = batch;
-    g.H = (int)H;
-    g.W = (int)W;
-    g.CW = (int)CW;
-    g.OH = (int)OH;
-    g.OW = (int)OW;
-    g.kh = kh;
-    g.kw = kw;
-    g.sh = stride_h;
-    g.sw = stride_w;
-    g.ph = pad_h;
-    g.pw = pad_w;
     if (const int rc_dev = check_device(name))
         return rc_dev;
     const hipError_t e = lowbit::launch_im2col_packed(planes, Fp, Bp, g, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess)
+        return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
+    return LB_OK;
+}
+
+int conv_gemm(int kind, int64_t M, const uint64_t *Ap, const uint64_t *Fp, int64_t batch, int64_t H, int64_t W,
+              int64_t C, int kh, int kw, int stride_h, int stride_w, int pad_h, int pad_w, int32_t *Cout, int64_t ldc,
+              void *stream)
+{
+    const char *name = "conv_gemm";
+    if (kind < 0 || kind > 2)
+        return fail(LB_EINVAL, "%s: kind=%d must be 0 (BNN), 1 (TNN) or 2 (TBN)", name, kind);
+    lowbit::Im2colGeom g;
+    bool empty;
+    int rc = check_conv_geom(name, batch, H, W, C, kh, kw, stride_h, stride_w, pad_h, pad_w, &g, &empty);
+    if (rc != LB_OK)
+        return rc;
+    if (M < 0)
+        return fail(LB_EINVAL, "%s: M=%lld must be >= 0", name, (long long)M);
+    if (kind == lowbit::KIND_TBN)
+        return fail(LB_EUNSUPPORTED,
+                    "%s: the ternary-binary kernel keeps the binary operand (here the feature map) in scalar registers, "
+                    "where it cannot be gathered; use im2col_packed + gemm_tbn",
+                    name);
+    if (empty || M == 0)
+        return LB_OK;
+    const int64_t N = batch * g.OH * g.OW, K = (int64_t)kh * kw * C;  // both bounded by check_conv_geom
+    if (N > kMaxExtent)
+        return fail(LB_EOVERFLOW, "%s: %lld output pixels exceed 2^31-1", name, (long long)N);
+    rc = check_gemm(name, M, N, K, Ap, Fp, Cout, ldc, &empty);
+    if (rc != LB_OK)
+        return rc;
+    if (const int rc_dev = check_device(name))
+        return rc_dev;
+    int count = 0;
+    const lowbit::GemmVariant *tab = lowbit::gemm_variants(kind, &count);
+    lowbit::GemmArgs a;
+    a.Sp = reinterpret_cast<const uint32_t *>(Ap);
+    a.rowsS = (int)M;
+    a.Vp = reinterpret_cast<const uint32_t *>(Fp);
+    a.rowsV = (int)N;
+    a.KW = (int)(K / 64);
+    a.K = (int)K;
+    a.C = Cout;
+    a.ldc = ldc;
+    a.stream = static_cast<hipStream_t>(stream);
+    const int fv = forced_variant(kind);
+    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
+    const hipError_t e = tab[v].launch_conv(a, g);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
     return LB_OK;

@@ -106,14 +106,15 @@ template <int KIND, int TV, int KG> struct TileLds {
 // accum: the results are added to C with integer atomics (depth-split launches into a cleared C) instead of stored.  TRM selects where product
 // (s, v) goes: 0 -> C[s*ldc + v], 1 -> C[v*ldc + s] (or the re-quantized output), 2 -> decided by tr_rt at run time
 // (workgroup-uniform), for launches that mix both orientations.
-template <int KIND, int TS, int TV, int WAVES, int KG, int SG, int TRM>
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG, int TRM, bool CONV = false>
 __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, const uint32_t *__restrict__ Vp,
                                                int rowsS, int rowsV, int KW, int ldk, int K,
                                                int32_t *__restrict__ C, int64_t ldc, int sb, int vb, bool tr_rt,
                                                bool c16, bool accum,
                                                const int32_t *__restrict__ q_lo, const int32_t *__restrict__ q_hi,
                                                uint64_t *__restrict__ q_out, int q_planes,
-                                               typename TileLds<KIND, TV, KG>::VVec *lds_base, int32_t *nnz_lds)
+                                               typename TileLds<KIND, TV, KG>::VVec *lds_base, int32_t *nnz_lds,
+                                               const Im2colGeom *cg = nullptr)
 {
     using T = Traits<KIND>;
     constexpr int SD = T::SD, VD = T::VD;
@@ -172,17 +173,100 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
         for (int e = threadIdx.x; e < NV; e += 64 * WAVES)
             nnz_lds[e] = 0;
     }
+    // Convolution (CONV): V string v is output pixel (b, oy, ox) and its depth word kg is channel word cw of the input
+    // pixel under window tap (ky, kx), in the depth order (ky, kx, c) of the unrolled operand, or zero in the
+    // padding -- the words are gathered from the channel-packed feature map while the tile is staged, the unrolled
+    // operand is never written.  The units a thread stages are consecutive depth words of ONE V string (asserted
+    // below), so the thread keeps one pixel: its window origin and the entry index of that origin in the map.  The tap
+    // of the next depth word is wave-uniform and advances by KG words per stage without divisions.  When the channel
+    // words per pixel are a multiple of KG, all words of a stage lie under one tap and share one bounds check and one
+    // address (the vector ALU is what bounds this kernel, so address arithmetic per word would cost its share of it:
+    // measured +10 % on the 3 x 3 x 512 layer, against +3 % this way).
+    static_assert(!CONV || (UPW <= KG && KG % UPW == 0), "a thread's staging units must share a V string");
+    int c_iy0 = 0, c_ix0 = 0, c_ky = 0, c_kx = 0, c_cw = 0;
+    int64_t c_base = 0;
+    bool c_ok = false, c_fast = false;
+    if constexpr (CONV) {
+        const int u0 = wave * UPW;
+        const int vseg = u0 / KG, g0 = u0 % KG;
+        const int v = v0 + vseg * 64 + lane;
+        c_ok = v < rowsV;
+        const int vv = c_ok ? v : 0;
+        const int per = cg->OH * cg->OW;
+        const int b = vv / per, rem = vv - b * per;
+        const int oy = rem / cg->OW, ox = rem - oy * cg->OW;
+        c_iy0 = oy * cg->sh - cg->ph;
+        c_ix0 = ox * cg->sw - cg->pw;
+        c_base = (((int64_t)b * cg->H + c_iy0) * cg->W + c_ix0) * cg->CW;  // may point outside the map; used in bounds only
+        const int tap = g0 / cg->CW;
+        c_cw = g0 - tap * cg->CW;
+        c_ky = tap / cg->kw;
+        c_kx = tap - c_ky * cg->kw;
+        c_fast = cg->CW % KG == 0;
+    }
     auto fetch = [&](int kg0) {
+        if constexpr (CONV) {
+            const int g0 = (wave * UPW) % KG;
+            if (c_fast) {
+                // one tap for the whole stage
+                const int iy = c_iy0 + c_ky, ix = c_ix0 + c_kx;
+                const bool in = c_ok && (unsigned)iy < (unsigned)cg->H && (unsigned)ix < (unsigned)cg->W;
+                const VVec *src = Vv + c_base + ((int64_t)c_ky * cg->W + c_kx) * cg->CW + c_cw;
 #pragma unroll
-        for (int j = 0; j < UPW; ++j) {
-            const int u = wave * UPW + j;
-            const int vseg = u / KG, g = u % KG;
-            const int v = v0 + vseg * 64 + lane;
-            const int kg = kg0 + g;
-            VVec e = zero_of(VVec{});
-            if (v < rowsV && kg < KW)
-                e = Vv[(int64_t)v * ldk + kg];
-            pre[j] = e;
+                for (int j = 0; j < UPW; ++j) {
+                    VVec e = zero_of(VVec{});
+                    if (in && kg0 + g0 + j < KW)
+                        e = src[j];
+                    pre[j] = e;
+                }
+                c_cw += KG;
+                if (c_cw >= cg->CW) {
+                    c_cw -= cg->CW;
+                    if (++c_kx == cg->kw) {
+                        c_kx = 0;
+                        ++c_ky;
+                    }
+                }
+            } else {
+                // general case: walk the tap word by word (scalar state), one bounds check and address per word
+                int ky = c_ky, kx = c_kx, cw = c_cw;
+#pragma unroll
+                for (int j = 0; j < UPW; ++j) {
+                    const int iy = c_iy0 + ky, ix = c_ix0 + kx;
+                    VVec e = zero_of(VVec{});
+                    if (c_ok && kg0 + g0 + j < KW && (unsigned)iy < (unsigned)cg->H && (unsigned)ix < (unsigned)cg->W)
+                        e = Vv[c_base + ((int64_t)ky * cg->W + kx) * cg->CW + cw];
+                    pre[j] = e;
+                    if (++cw == cg->CW) {
+                        cw = 0;
+                        if (++kx == cg->kw) {
+                            kx = 0;
+                            ++ky;
+                        }
+                    }
+                }
+                // the thread's first word of the next stage is KG words further down the depth
+                c_cw += KG;
+                while (c_cw >= cg->CW) {
+                    c_cw -= cg->CW;
+                    if (++c_kx == cg->kw) {
+                        c_kx = 0;
+                        ++c_ky;
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < UPW; ++j) {
+                const int u = wave * UPW + j;
+                const int vseg = u / KG, g = u % KG;
+                const int v = v0 + vseg * 64 + lane;
+                const int kg = kg0 + g;
+                VVec e = zero_of(VVec{});
+                if (v < rowsV && kg < KW)
+                    e = Vv[(int64_t)v * ldk + kg];
+                pre[j] = e;
+            }
         }
     };
     auto commit = [&](int buf) {
@@ -539,6 +623,56 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_popc_kernel(const uint32_t *_
                                                             c16 != 0, false, q_lo, q_hi, q_out, q_planes, lds, nnz_lds);
 }
 
+// Convolution as an implicit product: the kernel above with the V operand gathered from the channel-packed feature
+// map (see the tile routine); A (the filters) is on the scalar side, C is M x N row-major with N = batch * OH * OW.
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
+__global__ __launch_bounds__(64 * WAVES) void gemm_popc_conv_kernel(const uint32_t *__restrict__ Sp,
+                                                                    const uint32_t *__restrict__ Fp, int rowsS, int rowsV,
+                                                                    int KW, int K, int32_t *__restrict__ C, int64_t ldc,
+                                                                    int nSB, int nVB, int tiles_per_xcd, int vb_fastest,
+                                                                    const Im2colGeom geom)
+{
+    using L = TileLds<KIND, TV, KG>;
+    __shared__ typename L::VVec lds[2 * L::STAGE];
+    __shared__ int32_t nnz_lds[L::NNZ];
+    const int bid = blockIdx.x;
+    const int idx = (bid & 7) * tiles_per_xcd + (bid >> 3);
+    if ((bid >> 3) >= tiles_per_xcd || idx >= nSB * nVB)
+        return;
+    int vb, sb;
+    if (vb_fastest) {
+        sb = idx / nVB;
+        vb = idx - sb * nVB;
+    } else {
+        vb = idx / nSB;
+        sb = idx - vb * nSB;
+    }
+    gemm_popc_tile<KIND, TS, TV, WAVES, KG, SG, 0, true>(Sp, Fp, rowsS, rowsV, KW, KW, K, C, ldc, sb, vb, false, false,
+                                                         false, nullptr, nullptr, nullptr, 0, lds, nnz_lds, &geom);
+}
+
+template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
+hipError_t launch_conv(const GemmArgs &a, const Im2colGeom &g)
+{
+    if constexpr (KIND == KIND_BNN || KIND == KIND_TNN) {
+        const int nSB = (a.rowsS + WAVES * TS - 1) / (WAVES * TS);
+        const int nVB = (a.rowsV + 64 * TV - 1) / (64 * TV);
+        const int64_t tiles = (int64_t)nSB * nVB;
+        const int tiles_per_xcd = (int)((tiles + 7) / 8);
+        const int64_t grid = (int64_t)tiles_per_xcd * 8;
+        if (grid > 0x7fffffffLL)
+            return hipErrorInvalidConfiguration;
+        // the feature map is the smaller operand whenever the window has more than one tap: walk the S blocks of
+        // one V tile first, as for a materialised operand
+        hipLaunchKernelGGL((gemm_popc_conv_kernel<KIND, TS, TV, WAVES, KG, SG>), dim3((unsigned)grid), dim3(64 * WAVES),
+                           0, a.stream, a.Sp, a.Vp, a.rowsS, a.rowsV, a.KW, a.K, a.C, a.ldc, nSB, nVB, tiles_per_xcd, 0,
+                           g);
+        return hipGetLastError();
+    } else {
+        return hipErrorNotSupported;  // the gathered operand must be on the vector side
+    }
+}
+
 // Grouped launch: many independent small problems in one grid.  The table (built on the host by plan_group) maps
 // each workgroup id to a problem record and the record gives the tile's place inside that problem.
 template <int KIND, int TS, int TV, int WAVES, int KG, int SG>
@@ -642,11 +776,13 @@ hipError_t launch(const GemmArgs &a)
 
 #define LB_VARIANT(RANK, KIND, TS, TV, WAVES, KG, SG)                                               \
     {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, RANK, TS * WAVES, 64 * TV,           \
-     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, 0, 0}
+     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, 0, 0,  \
+     &launch_conv<KIND, TS, TV, WAVES, KG, SG>}
 // latency-bound instance: taken for problems of at most SMALL_MAX tiles of 16 x 64 and at least MIN_KW depth words
 #define LB_SMALL(SMALL_MAX, MIN_KW, KIND, TS, TV, WAVES, KG, SG)                                    \
     {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, 0, TS * WAVES, 64 * TV,              \
-     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, SMALL_MAX, MIN_KW}
+     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, SMALL_MAX, MIN_KW, \
+     &launch_conv<KIND, TS, TV, WAVES, KG, SG>}
 
 // rank: preference of the shape-based selection (the highest rank wins among the variants that yield enough
 // workgroups, otherwise the ranked variant with the most workgroups; 0 = only reachable through lb_set_variant).

@@ -645,11 +645,14 @@ template <int KIND> hipError_t launch_kind(const SkinnyArgs &a, bool tr)
         const size_t lds = stream_lds_bytes<KIND>(a);
         // Measured (cold operand, 4096 .. 131072 rows, depth 4096 .. 32768): the streaming kernel is 0-20 % faster than
         // the chunked one except on the longest ternary-binary streams, which the chunked kernel already runs at the
-        // rate of a read-only kernel; two rows per wave pay from 32768 rows on (binary X: from 16384).
+        // rate of a read-only kernel; two rows per wave pay from 32768 rows on (binary X: from 16384; ternary x ternary:
+        // never).
         constexpr bool kTbn = KIND == KIND_TBN || KIND == KIND_TBN_SV;
         const bool chunked_better = cfg < 0 && kTbn && a.rowsX >= 65536 && a.KW >= 256;
         if (lds > 0 && !chunked_better) {
-            const int two_from = KIND == KIND_BNN ? 16384 : 32768;
+            // ternary x ternary keeps one row per wave at every size (two gain nothing on long streams and lose 8 %
+            // at 16384 rows)
+            const int two_from = KIND == KIND_BNN ? 16384 : KIND == KIND_TNN ? 0x7fffffff : 32768;
             const StreamShape sh = cfg >= kChunkedConfigs ? kStreamForced[cfg - kChunkedConfigs]
                                                           : StreamShape{a.rowsX >= two_from ? 2 : 1, 4, 4};
             return launch_stream<KIND>(a, tr, lds, sh);

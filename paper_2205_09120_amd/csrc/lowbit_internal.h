@@ -31,6 +31,8 @@ struct GemmArgs {
     int q_planes = 0;
 };
 
+struct Im2colGeom;
+
 struct GemmVariant {
     const char *name;
     int rank;          // preference of the shape-based selection, 0 = manual only
@@ -39,6 +41,10 @@ struct GemmVariant {
     hipError_t (*launch_transposed)(const GemmArgs &);
     int small_max;     // > 0: chosen for problems of at most this many 16 x 64 tiles (first match in table order) ...
     int small_min_kw;  // ... whose depth is at least this many 64-bit words
+    // the same instance with the V operand gathered from a channel-packed feature map (convolution without the
+    // unrolled operand; a.Vp is the packed map, a.rowsV the output pixels); hipErrorNotSupported for the kinds whose
+    // gathered operand would sit on the scalar side
+    hipError_t (*launch_conv)(const GemmArgs &, const Im2colGeom &);
 };
 
 const GemmVariant *gemm_variants(int kind, int *count);

@@ -145,3 +145,114 @@ def test_two_convolution_layers_stay_packed(out_planes):
     torch.cuda.synchronize()
     got = C2.cpu().numpy().reshape(F2, nb, OH, OW).transpose(1, 2, 3, 0)
     assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ convolution as an implicit product (conv_gemm)
+
+CONV_GEOMS = GEOMS + [
+    (2, 20, 17, 64, 3, 3, 1, 1, 1, 1),      # 680 output pixels: several V tiles and a ragged last one
+    (1, 33, 31, 128, 3, 3, 2, 2, 1, 1),     # stride 2 with padding
+    (3, 11, 13, 64, 1, 5, 1, 2, 0, 2),      # flat window, channel words < words per stage
+    (1, 40, 40, 320, 3, 3, 1, 1, 1, 1),     # 5 channel words: taps do not align with the staging chunks
+]
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS)
+def test_conv_gemm_ternary_matches_direct_convolution(geom):
+    """conv_gemm (ternary filters x ternary map) against the definition of the convolution, for every tile variant."""
+    nb, H, W, C, kh, kw, sh, sw, ph, pw = geom
+    F = 70
+    fmap = _fmap("tnn", geom, seed=31 + sum(geom))
+    filt, _ = synth.make_custom("tnn", F, 1, kh * kw * C, seed=33)
+    OH, OW = oi.out_size(H, W, kh, kw, sh, sw, ph, pw)
+    N = nb * OH * OW
+    want = oi.conv2d_direct(fmap, filt.reshape(F, kh, kw, C), sh, sw, ph, pw)
+    Ap = lb.pack_a("tnn", torch.from_numpy(filt).cuda())
+    Fp = lb.pack_ternary(torch.from_numpy(fmap).cuda(), nb * H * W, C, C, 1)
+    try:
+        for v in list(range(lb.lb_num_variants("tnn"))) + [-1]:
+            say(f"conv_gemm tnn geom={geom} variant={v}")
+            lb.lb_set_variant("tnn", v)
+            Cm = torch.full((F, N + 2), -3, dtype=torch.int32, device="cuda")
+            lb.conv_gemm("tnn", F, Ap, Fp, nb, H, W, C, kh, kw, sh, sw, ph, pw, Cm, N + 2)
+            torch.cuda.synchronize()
+            got = Cm.cpu().numpy()
+            assert np.all(got[:, N:] == -3)
+            assert np.array_equal(got[:, :N].reshape(F, nb, OH, OW).transpose(1, 2, 3, 0), want), v
+    finally:
+        lb.lb_set_variant("tnn", -1)
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS[:8])
+def test_conv_gemm_binary_pads_with_plus_one(geom):
+    """Binary filters x binary map: a binary map has no code for 0, positions outside the map count as +1.  Checked
+    against the direct convolution of a map that is padded with +1 explicitly (and has no padding of its own left)."""
+    nb, H, W, C, kh, kw, sh, sw, ph, pw = geom
+    say(f"conv_gemm bnn geom={geom}")
+    F = 33
+    fmap = _fmap("bnn", geom, seed=41 + sum(geom))
+    filt, _ = synth.make_custom("bnn", F, 1, kh * kw * C, seed=43)
+    padded = np.ones((nb, H + 2 * ph, W + 2 * pw, C), dtype=np.int8)
+    padded[:, ph:ph + H, pw:pw + W, :] = fmap
+    want = oi.conv2d_direct(padded, filt.reshape(F, kh, kw, C), sh, sw, 0, 0)
+    OH, OW = oi.out_size(H, W, kh, kw, sh, sw, ph, pw)
+    Ap = lb.pack_a("bnn", torch.from_numpy(filt).cuda())
+    Fp = lb.pack_binary(torch.from_numpy(fmap).cuda(), nb * H * W, C, C, 1)
+    Cm = lb.conv_gemm("bnn", F, Ap, Fp, nb, H, W, C, kh, kw, sh, sw, ph, pw)
+    torch.cuda.synchronize()
+    got = Cm.cpu().numpy().reshape(F, nb, OH, OW).transpose(1, 2, 3, 0)
+    assert np.array_equal(got, want)
+    # the two-step lowering writes the same values
+    Bp = lb.im2col_packed(Fp, 1, nb, H, W, C, kh, kw, sh, sw, ph, pw)
+    C2 = lb.gemm_bnn(F, nb * OH * OW, kh * kw * C, Ap, Bp)
+    torch.cuda.synchronize()
+    assert torch.equal(C2, Cm)
+
+
+def test_conv_gemm_headline_geometry():
+    """Batch 16 of 56x56x512 maps, 1024 filters of 3x3x512, padding 1 -- the layer behind the benchmark's 1024 x 50176
+    x 4608 product -- at full size in the default launch configuration: sampled outputs recomputed by the oracle from
+    the unrolled definition, and every output equal to the product on the materialised operand."""
+    nb, H, W, C, kh, kw, F = 16, 56, 56, 512, 3, 3, 1024
+    say("conv_gemm headline geometry 16x56x56x512, 1024 filters 3x3, pad 1")
+    rng = np.random.default_rng(6)
+    fmap = synth.draw_ternary(rng, (nb * H * W, C), 0.5).reshape(nb, H, W, C)
+    filt = synth.draw_ternary(rng, (F, kh * kw * C), 0.5)
+    Ap = lb.pack_a("tnn", torch.from_numpy(filt).cuda())
+    Fp = lb.pack_ternary(torch.from_numpy(fmap).cuda(), nb * H * W, C, C, 1)
+    N, K = nb * H * W, kh * kw * C
+    Cm = lb.conv_gemm("tnn", F, Ap, Fp, nb, H, W, C, kh, kw, 1, 1, 1, 1)
+    Bp = lb.im2col_packed(Fp, 2, nb, H, W, C, kh, kw, 1, 1, 1, 1)
+    C2 = lb.gemm_tnn(F, N, K, Ap, Bp)
+    torch.cuda.synchronize()
+    assert torch.equal(Cm, C2)
+    # sampled pixels (corners, edges, interior) x all filters: columns of the unrolled operand built by the definition
+    pix = [(0, 0, 0), (0, 0, 55), (0, 55, 0), (15, 55, 55), (3, 17, 0), (7, 0, 31), (9, 28, 28)]
+    pix += [tuple(int(v) for v in p) for p in np.stack([rng.integers(0, nb, 40), rng.integers(0, H, 40),
+                                                        rng.integers(0, W, 40)], axis=1)]
+    cols = np.zeros((K, len(pix)), dtype=np.int8)
+    for j, (b, oy, ox) in enumerate(pix):
+        for ky in range(kh):
+            for kx in range(kw):
+                iy, ix = oy + ky - 1, ox + kx - 1
+                if 0 <= iy < H and 0 <= ix < W:
+                    cols[(ky * kw + kx) * C:(ky * kw + kx + 1) * C, j] = fmap[b, iy, ix]
+    want = oracle.gemm(filt, cols)                                   # (F, samples)
+    idx = torch.tensor([(b * H + oy) * W + ox for (b, oy, ox) in pix], device="cuda")
+    got = Cm[:, idx].cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_conv_gemm_argument_rules():
+    say("conv_gemm: ternary-binary operands are refused, empty problems are no-ops")
+    Fp = torch.zeros(64, dtype=torch.int64, device="cuda")
+    Ap = torch.zeros(64, dtype=torch.int64, device="cuda")
+    with pytest.raises(lb.LowbitError) as e:
+        lb.conv_gemm("tbn", 4, Ap, Fp, 1, 2, 2, 64, 1, 1)
+    assert e.value.status == lb.LB_EUNSUPPORTED
+    lb.conv_gemm("tnn", 0, None, None, 1, 2, 2, 64, 1, 1)
+    lb.conv_gemm("tnn", 4, None, None, 0, 2, 2, 64, 1, 1)
+    lb.conv_gemm("tnn", 4, None, None, 1, 2, 2, 64, 3, 3)            # window larger than the unpadded map
+    with pytest.raises(lb.LowbitError) as e:
+        lb.conv_gemm("tnn", 4, Ap, Fp, 1, 2, 2, 100, 1, 1)
+    assert e.value.status == lb.LB_EUNSUPPORTED                      # channels not a multiple of 64
