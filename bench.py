@@ -399,6 +399,15 @@ def main() -> int:
         packs["ternary_50176x4608_depth_contiguous"] = {"us": tbc * 1e6, "gbs": (B.nbytes + Bp.numel() * 8) / tbc / 1e9}
         packs["binary_50176x4608_depth_contiguous"] = {"us": tbcb * 1e6, "gbs": (B.nbytes + Bb.numel() * 8) / tbcb / 1e9}
         del Bb
+        # the cfg4 source (231 MB) fits the 256 MB last-level cache, so back-to-back calls on it are partly served from
+        # there; a source of 461 MB (100000 strings of the same depth) shows the rate from HBM proper
+        big_rows = 100000
+        big_src = torch.randint(-1, 2, (K, big_rows), dtype=torch.int8, device="cuda")
+        big_dst = torch.empty(lb.packed_ternary_bytes(big_rows, K) // 8, dtype=torch.int64, device="cuda")
+        tbig = T.dev("pack_ternary_100000x4608_strided", lambda: lb.pack_ternary(big_src, big_rows, K, 1, big_rows, big_dst), 2)
+        packs["ternary_100000x4608_depth_strided_beyond_last_level_cache"] = {
+            "us": tbig * 1e6, "gbs": (big_src.numel() + big_dst.numel() * 8) / tbig / 1e9}
+        del big_src, big_dst
         for v in packs.values():
             v["frac_of_hbm_peak"] = v["gbs"] / HBM_PEAK_GBS
         lb.pack_ternary(dB, N, K, 1, N, Bp)  # restore the real operand

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "lowbit_internal.h"
 
 namespace lowbit {
@@ -116,8 +118,14 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
                                                             int64_t nRB)
 {
     constexpr int ED = TERNARY ? 4 : 2;       // dwords per output entry
-    __shared__ uint32_t tile[128][8 * ED + 1];
-
+    // LDS tile: 128 strings x 8 entries (one entry = one depth word of a string: 16 bytes ternary, 8 bytes binary).
+    // String quad*4 + i sits in row i*32 + quad, and entry e of row r in slot e ^ ((r >> SW) & 7): the 16 (ternary) or
+    // 32 (binary) lanes that one LDS write processes together hold consecutive rows and the same e, and the lanes of
+    // one read hold all 8 entries of 2 (4) rows whose row numbers differ in the bits below SW -- both then touch every
+    // bank exactly once.
+    using Entry = typename std::conditional<TERNARY, uint4, uint2>::type;
+    constexpr int SW = TERNARY ? 1 : 2;
+    __shared__ Entry tile[128 * 8];
     const int64_t rb = blockIdx.x % nRB, wb = blockIdx.x / nRB;
     const int quad = threadIdx.x & 31, wl = threadIdx.x >> 5;
     const int64_t r0 = rb * 128 + quad * 4;
@@ -191,26 +199,28 @@ __global__ __launch_bounds__(256) void pack_kstrided_kernel(const int8_t *__rest
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        uint32_t *e = &tile[quad * 4 + i][wl * ED];
-        if (TERNARY) {
-            e[0] = plo[i];
-            e[1] = phi[i];
-            e[2] = nlo[i];
-            e[3] = nhi[i];
-        } else {
-            e[0] = nlo[i];
-            e[1] = nhi[i];
-        }
+        const int row = i * 32 + quad;
+        Entry e;
+        if constexpr (TERNARY)
+            e = make_uint4(plo[i], phi[i], nlo[i], nhi[i]);
+        else
+            e = make_uint2(nlo[i], nhi[i]);
+        tile[row * 8 + (wl ^ ((row >> SW) & 7))] = e;
     }
     __syncthreads();
-    // write out: 8*ED dwords per string are contiguous in dst
-    constexpr int DW = 8 * ED;
-    for (int idx = threadIdx.x; idx < 128 * DW; idx += 256) {
-        const int rl = idx / DW, d = idx % DW;
+    // write out: the 8 entries of a string are contiguous in dst; a thread moves one entry per round
+    constexpr int G = TERNARY ? 2 : 4;  // strings whose entries one LDS read processes together
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int e = idx & 7, t = idx >> 3;
+        const int rl = (t % G) * 4 + ((t / G) % 4) + (t / (4 * G)) * (4 * G);  // string within the tile
+        const int row = (rl & 3) * 32 + (rl >> 2);
+        const Entry v = tile[row * 8 + (e ^ ((row >> SW) & 7))];
         const int64_t r = rb * 128 + rl;
-        const int64_t ww = wb * 8 + d / ED;
+        const int64_t ww = wb * 8 + e;
         if (r < rows && ww < KW)
-            dst[(r * KW + ww) * ED + d % ED] = tile[rl][d];
+            *reinterpret_cast<Entry *>(dst + (r * KW + ww) * ED) = v;
     }
 }
 
