@@ -65,9 +65,20 @@ template <> __device__ __forceinline__ uint4 zero_entry<uint4>() { return zero4(
 __device__ __forceinline__ uint4 nz_neg(uint4 e) { return make_uint4(e.x | e.z, e.y | e.w, e.z, e.w); }
 __device__ __forceinline__ uint2 nz_neg(uint2 e) { return e; }
 
+// Value of v held by lane (l ^ BIT).  Within a half of the wave (BIT < 32) one LDS-pipe swizzle with an immediate
+// pattern, no address arithmetic; across the halves a permute through the byte address of lane l ^ 32 (swap32, computed
+// once per kernel).
+template <int BIT> __device__ __forceinline__ int32_t lane_xor(int32_t v, int swap32)
+{
+    if constexpr (BIT == 32)
+        return __builtin_amdgcn_ds_bpermute(swap32, v);
+    else
+        return __builtin_amdgcn_ds_swizzle(v, (BIT << 10) | 0x1f);  // bit-mask mode: and 0x1f, or 0, xor BIT
+}
+
 // Sum val[0..CNT) over the lanes that differ in bit BIT and below; afterwards val[0] of lane l holds the total of
 // the value whose index is formed by the lane bits consumed while CNT > 1 (most significant first).
-template <int CNT, int BIT> __device__ __forceinline__ void reduce_halving(int32_t *val, int lane)
+template <int CNT, int BIT> __device__ __forceinline__ void reduce_halving(int32_t *val, int lane, int swap32)
 {
     if constexpr (BIT >= 1) {
         if constexpr (CNT > 1) {
@@ -77,12 +88,12 @@ template <int CNT, int BIT> __device__ __forceinline__ void reduce_halving(int32
             for (int i = 0; i < HALF; ++i) {
                 const int32_t send = upper ? val[i] : val[i + HALF];
                 const int32_t keep = upper ? val[i + HALF] : val[i];
-                val[i] = keep + __shfl_xor(send, BIT, 64);
+                val[i] = keep + lane_xor<BIT>(send, swap32);
             }
-            reduce_halving<HALF, BIT / 2>(val, lane);
+            reduce_halving<HALF, BIT / 2>(val, lane, swap32);
         } else {
-            val[0] += __shfl_xor(val[0], BIT, 64);
-            reduce_halving<1, BIT / 2>(val, lane);
+            val[0] += lane_xor<BIT>(val[0], swap32);
+            reduce_halving<1, BIT / 2>(val, lane, swap32);
         }
     }
 }
@@ -231,7 +242,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(const void *__r
         }
 
     // halving butterfly: at lane-bit b the lanes with the bit set keep the upper half of the values
-    reduce_halving<V, 32>(val, lane);
+    reduce_halving<V, 32>(val, lane, (lane ^ 32) << 2);
     // lane l now holds the total of value index (l >> (6 - log2 V)); one lane of each group stores it
     constexpr int GROUP = 64 / V;
     if ((lane % GROUP) == 0) {
@@ -395,17 +406,55 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_stream_kernel(const vo
     };
 
     const int rounds = (entries + NT * YU - 1) / (NT * YU);
-    for (int round = 0; round + 1 < rounds; ++round) {
-        y_load(round);
-        y_store(round);
-    }
-    y_load(rounds - 1);
+    // whole problem (all NS strings, depth a multiple of the step, whole rounds): no clamps, no masks
+    const bool y_whole = KFULL && rowsY - y0 >= NS && entries % (NT * YU) == 0;
+    auto y_load_whole = [&](int round) {
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        issue(d);
-    y_store(rounds - 1);
+        for (int i = 0; i < YU; ++i) {
+            const int e = (round * YU + i) * NT + tid;
+            const int w = e & (SW - 1), t = e / SW;
+            const int n = t & (NS - 1), jb = t / NS;
+            const int slot = (W == 2 && YTER) ? (w & 63) * 2 + (w >> 6) : w;
+            yv[i] = Yp[(int64_t)(y0 + n) * KW + jb * SW + slot];
+        }
+    };
+    auto y_store_whole = [&](int round) {
+#pragma unroll
+        for (int i = 0; i < YU; ++i) {
+            const int e = (round * YU + i) * NT + tid;
+            const YE y = nz_neg(yv[i]);
+            ylds[e] = y;
+            if constexpr (KIND == KIND_TBN_SV) {
+                const int cnt = __builtin_popcount(y.x) + __builtin_popcount(y.y);
+                if (cnt)
+                    atomicAdd(&ynnz[(e / SW) & (NS - 1)], cnt);
+            }
+        }
+    };
+    if (y_whole) {
+        for (int round = 0; round + 1 < rounds; ++round) {
+            y_load_whole(round);
+            y_store_whole(round);
+        }
+        y_load_whole(rounds - 1);
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            issue(d);
+        y_store_whole(rounds - 1);
+    } else {
+        for (int round = 0; round + 1 < rounds; ++round) {
+            y_load(round);
+            y_store(round);
+        }
+        y_load(rounds - 1);
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            issue(d);
+        y_store(rounds - 1);
+    }
     __syncthreads();
 
+    const int swap32 = (lane ^ 32) << 2;  // byte address of the partner lane in the other half of the wave
     int32_t acc[T::ACC][R][NS];
     int32_t nnz[R];
     auto clear = [&]() {
@@ -435,7 +484,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_stream_kernel(const vo
                 else
                     val[r * NS + n] = nnz[r] - 2 * acc[0][r][n];
             }
-        reduce_halving<V, 32>(val, lane);
+        reduce_halving<V, 32>(val, lane, swap32);
         constexpr int GROUP = 64 / V;
         if ((lane % GROUP) == 0) {
             const int idx = lane / GROUP;
