@@ -16,7 +16,8 @@ extern "C" {
  * Calibration kernels for the benchmark: what the machine sustains for the two bounds of the rooflines.  The
  * caller times them (HIP events on `stream`).
  *   lb_calib_valu     runs lb_calib_valu_lane_instr(mix, iters, waves_per_simd) lane-instructions of independent
- *                     chains on registers, waves_per_simd (1..8) waves on every SIMD of the device.  mix 0: the binary
+ *                     chains on registers, waves_per_simd (1..8) waves on every SIMD of the device, iters in
+ *                     [1, 2^24] (the count is 0 for arguments outside these ranges).  mix 0: the binary
  *                     kernel's pair (v_xor_b32 with a scalar source, v_bcnt_u32_b32), 1: the ternary kernel's four
  *                     (v_and_b32 and v_bitop3_b32 with a scalar source, 2 x v_bcnt_u32_b32), 2: the ternary-binary
  *                     kernel's pair (v_bitop3_b32 with a scalar source, v_bcnt_u32_b32); single instruction forms:

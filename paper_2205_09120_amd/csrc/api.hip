@@ -1054,7 +1054,8 @@ size_t lb_calib_sink_bytes(void) { return (size_t)lowbit::calib_grid_blocks() * 
 
 int64_t lb_calib_valu_lane_instr(int mix, int64_t iters, int waves_per_simd)
 {
-    if (mix < 0 || mix >= lowbit::CALIB_NUM_MIXES || iters <= 0 || waves_per_simd < 1 || waves_per_simd > 8)
+    if (mix < 0 || mix >= lowbit::CALIB_NUM_MIXES || iters <= 0 || iters > (1 << 24) || waves_per_simd < 1 ||
+        waves_per_simd > 8)
         return 0;
     return lowbit::calib_valu_lane_instr(mix, iters, waves_per_simd);
 }
