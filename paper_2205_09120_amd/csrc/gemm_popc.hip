@@ -567,12 +567,15 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
 #pragma unroll
                 for (int i = 0; i < TS; ++i)
                     if (s0 + i < rowsS)
-                        C[(int64_t)(s0 + i) * ldc + v] = out[i];
+                        store_through(C + (int64_t)(s0 + i) * ldc + v, out[i]);
             } else {
                 int32_t *crow = C + (int64_t)v * ldc + s0;
                 if constexpr (TS % 4 == 0) {
                     if (s0 + TS <= rowsS) {
-                        // 128-bit stores through memcpy: they need no 16-byte alignment (odd ldc, odd N)
+                        // 128-bit stores through memcpy: they need no 16-byte alignment (odd ldc, odd N).  Plain stores:
+                        // a lane writes 16 bytes of a line that other waves complete later, and written through, those
+                        // pieces would reach memory one by one (measured 13 % slower on 1024 x 50176 x 4608); the L2
+                        // has to merge them.
 #pragma unroll
                         for (int i = 0; i < TS; i += 4) {
                             const int4 q = make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);
