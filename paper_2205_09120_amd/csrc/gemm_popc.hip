@@ -38,6 +38,7 @@ namespace lowbit {
 namespace {
 
 constexpr int kPadEntries = 4;  // LDS row padding, in entries
+constexpr int kComputeUnits = 256;  // MI355X
 
 template <int KIND> struct Traits;
 template <> struct Traits<KIND_BNN> { static constexpr int SD = 2, VD = 2, ACC = 1; };
@@ -524,6 +525,53 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
             }
             continue;
         }
+        if constexpr ((WAVES * TS + 4) * 64 * 4 <= (int)sizeof(VVec) * 2 * KG * STRIDE && TRM != 0) {
+            if (tr && !accum && !c16) {
+                // Lanes own rows of C here and hold TS consecutive columns of them: stored from the registers, every
+                // lane would write a 4 * TS byte piece of a line that other waves complete.  The workgroup's
+                // (WAVES*TS) x 64 results go through LDS instead (the tile buffers are free after the main loop) and
+                // leave as whole rows of the tile: 16 bytes per thread, consecutive threads on consecutive columns,
+                // written through the L2 when the launch is large enough for the write-back at its end to matter
+                // (measured: 1024 x 12544 x 4608 TBN 121 -> 111 us, 512 x 12544 x 2304 39.1 -> 34.9 us; launches of a few
+                // workgroups are 0.1 - 0.3 us faster with plain stores).
+                constexpr int SW = WAVES * TS, PITCH = SW + 4, CPR = SW / 4;
+                const bool through = gridDim.x >= 2 * kComputeUnits;
+                int32_t *stage = reinterpret_cast<int32_t *>(lds_base);
+                __syncthreads();  // every wave is done with the tile buffers (and with the staging of the previous t)
+                if constexpr (TS % 4 == 0) {
+#pragma unroll
+                    for (int i = 0; i < TS; i += 4)
+                        *reinterpret_cast<int4 *>(stage + lane * PITCH + wave * TS + i) =
+                            make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TS; ++i)
+                        stage[lane * PITCH + wave * TS + i] = out[i];
+                }
+                __syncthreads();
+                for (int e = threadIdx.x; e < 64 * CPR; e += 64 * WAVES) {
+                    const int vl = e / CPR, ch = e - vl * CPR;
+                    const int vv = v0 + t * 64 + vl, ss = sb * SW + ch * 4;
+                    if (vv < rowsV && ss < rowsS) {
+                        const int4 q = *reinterpret_cast<const int4 *>(stage + vl * PITCH + ch * 4);
+                        int32_t *dst = C + (int64_t)vv * ldc + ss;
+                        if (ss + 4 <= rowsS) {
+                            if (through)
+                                store_through16(dst, q.x, q.y, q.z, q.w);
+                            else
+                                __builtin_memcpy(dst, &q, 16);  // no 16-byte alignment needed
+                        } else {
+                            dst[0] = q.x;
+                            if (ss + 1 < rowsS)
+                                dst[1] = q.y;
+                            if (ss + 2 < rowsS)
+                                dst[2] = q.z;
+                        }
+                    }
+                }
+                continue;
+            }
+        }
         if (v < rowsV) {
             if (accum) {
 #pragma unroll
@@ -572,10 +620,11 @@ __device__ __forceinline__ void gemm_popc_tile(const uint32_t *__restrict__ Sp, 
                 int32_t *crow = C + (int64_t)v * ldc + s0;
                 if constexpr (TS % 4 == 0) {
                     if (s0 + TS <= rowsS) {
-                        // 128-bit stores through memcpy: they need no 16-byte alignment (odd ldc, odd N).  Plain stores:
-                        // a lane writes 16 bytes of a line that other waves complete later, and written through, those
-                        // pieces would reach memory one by one (measured 13 % slower on 1024 x 50176 x 4608); the L2
-                        // has to merge them.
+                        // (instances whose tile buffers cannot hold the staged results, and the 16-bit path above,
+                        // store from the registers.)  128-bit stores through memcpy: they need no 16-byte alignment
+                        // (odd ldc, odd N).  Plain stores: a lane writes 16 bytes of a line that other waves complete
+                        // later, and written through, those pieces would reach memory one by one (measured 13 % slower
+                        // on 1024 x 50176 x 4608); the L2 has to merge them.
 #pragma unroll
                         for (int i = 0; i < TS; i += 4) {
                             const int4 q = make_int4(out[i], out[i + 1], out[i + 2], out[i + 3]);

@@ -25,6 +25,17 @@ __device__ __forceinline__ void store_through(int32_t *p, int32_t v)
     *p = v;
 #endif
 }
+// 16 bytes at any 4-byte aligned global address
+__device__ __forceinline__ void store_through16(void *p, int32_t a, int32_t b, int32_t c, int32_t d)
+{
+    typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+    const i32x4 q = {a, b, c, d};
+#if LB_STORE_THROUGH
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(q) : "memory");
+#else
+    __builtin_memcpy(p, &q, 16);
+#endif
+}
 __device__ __forceinline__ void store_through(uint32_t *p, uint32_t v)
 {
 #if LB_STORE_THROUGH
