@@ -154,10 +154,10 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
     int best = -1, fallback = -1;
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
-        if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s)
+        if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s || KW < tab[i].small_min_kw)
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
-        const int64_t wanted = tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
+        const int64_t wanted = tab[i].wanted_wg > 0 ? tab[i].wanted_wg : tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
         if (wg >= wanted && (best < 0 || tab[i].rank > tab[best].rank))
             best = i;
         if (wg > fallback_wg) {

@@ -830,6 +830,11 @@ hipError_t launch(const GemmArgs &a)
     {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, RANK, TS * WAVES, 64 * TV,           \
      &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, 0, 0,  \
      &launch_conv<KIND, TS, TV, WAVES, KG, SG>}
+// ranked instance with conditions of its own: at least MIN_KW depth words and WANTED workgroups
+#define LB_VARIANT_IF(RANK, MIN_KW, WANTED, KIND, TS, TV, WAVES, KG, SG)                            \
+    {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, RANK, TS * WAVES, 64 * TV,           \
+     &launch<KIND, TS, TV, WAVES, KG, SG, false>, &launch<KIND, TS, TV, WAVES, KG, SG, true>, 0, MIN_KW, \
+     &launch_conv<KIND, TS, TV, WAVES, KG, SG>, WANTED}
 // latency-bound instance: taken for problems of at most SMALL_MAX tiles of 16 x 64 and at least MIN_KW depth words
 #define LB_SMALL(SMALL_MAX, MIN_KW, KIND, TS, TV, WAVES, KG, SG)                                    \
     {#KIND " ts" #TS " tv" #TV " w" #WAVES " kg" #KG " sg" #SG, 0, TS * WAVES, 64 * TV,              \
@@ -846,11 +851,14 @@ hipError_t launch(const GemmArgs &a)
 const GemmVariant kBnn[] = {
     LB_VARIANT(1, KIND_BNN, 4, 1, 4, 16, 8),
     LB_VARIANT(2, KIND_BNN, 8, 1, 4, 8, 4),
-    LB_VARIANT(4, KIND_BNN, 8, 2, 8, 8, 4),
+    LB_VARIANT(5, KIND_BNN, 8, 2, 8, 8, 4),
     LB_VARIANT(0, KIND_BNN, 8, 4, 8, 8, 4),
     LB_VARIANT(3, KIND_BNN, 8, 2, 4, 8, 4),
     LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8, 2),
     LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
+    // 32 x 128 tile with eight waves of four rows (see the ternary table): for products too small for the 64 x 128
+    // tile (512 x 8192 x 2304: 23.9 -> 21.7 us, 512 x 12544 x 2304: 34.6 -> 33.4 us)
+    LB_VARIANT_IF(4, 32, 1024, KIND_BNN, 4, 2, 8, 8, 4),
     LB_SMALL(64, 0, KIND_BNN, 1, 1, 4, 16, 8),
     LB_SMALL(160, 0, KIND_BNN, 1, 1, 8, 16, 8),
     LB_SMALL(300, 18, KIND_BNN, 1, 1, 8, 16, 8),
@@ -865,6 +873,11 @@ const GemmVariant kTnn[] = {
     LB_VARIANT(0, KIND_TNN, 8, 4, 4, 4, 1),
     LB_VARIANT(0, KIND_TNN, 8, 4, 4, 2, 1),
     LB_VARIANT(0, KIND_TNN, 8, 4, 8, 4, 2),
+    // 32 x 128 tile with eight waves of four rows: two waves of a workgroup on every SIMD, so that a workgroup keeps
+    // its SIMDs fed on its own when the launch drains and fewer of them are resident; half the accumulators per wave.
+    // Measured against the instances above: 1024 x 50176 x 4608 726 -> 719 us, 1024 x 12544 x 4608 203 -> 196 us,
+    // 512 x 12544 x 2304 61 -> 59 us; shallow products (18 depth words: three stages of 8, 8, 2) are slower with it.
+    LB_VARIANT_IF(5, 32, 1024, KIND_TNN, 4, 2, 8, 8, 4),
     LB_SMALL(300, 0, KIND_TNN, 1, 1, 8, 16, 4),
     LB_SMALL(600, 0, KIND_TNN, 2, 1, 8, 16, 4),
     LB_SMALL(1200, 0, KIND_TNN, 4, 1, 8, 16, 4),
@@ -872,7 +885,7 @@ const GemmVariant kTnn[] = {
 const GemmVariant kTbn[] = {
     LB_VARIANT(1, KIND_TBN, 4, 1, 4, 16, 8),
     LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 4),
-    LB_VARIANT(3, KIND_TBN, 8, 2, 8, 8, 4),
+    LB_VARIANT_IF(3, 0, 1024, KIND_TBN, 8, 2, 8, 8, 4),  // eight waves: half the workgroups of a four-wave tile fill the device
     LB_VARIANT(4, KIND_TBN, 8, 4, 8, 4, 1),
     LB_VARIANT(0, KIND_TBN, 8, 4, 4, 4, 4),
     LB_VARIANT(0, KIND_TBN, 8, 2, 4, 8, 4),

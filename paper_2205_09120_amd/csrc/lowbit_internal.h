@@ -36,14 +36,6 @@ __device__ __forceinline__ void store_through16(void *p, int32_t a, int32_t b, i
     __builtin_memcpy(p, &q, 16);
 #endif
 }
-__device__ __forceinline__ void store_through(uint32_t *p, uint32_t v)
-{
-#if LB_STORE_THROUGH
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#else
-    *p = v;
-#endif
-}
 #endif
 
 
@@ -81,11 +73,12 @@ struct GemmVariant {
     hipError_t (*launch)(const GemmArgs &);
     hipError_t (*launch_transposed)(const GemmArgs &);
     int small_max;     // > 0: chosen for problems of at most this many 16 x 64 tiles (first match in table order) ...
-    int small_min_kw;  // ... whose depth is at least this many 64-bit words
+    int small_min_kw;  // ... whose depth is at least this many 64-bit words (ranked variants: taken only from this depth on)
     // the same instance with the V operand gathered from a channel-packed feature map (convolution without the
     // unrolled operand; a.Vp is the packed map, a.rowsV the output pixels); hipErrorNotSupported for the kinds whose
     // gathered operand would sit on the scalar side
     hipError_t (*launch_conv)(const GemmArgs &, const Im2colGeom &);
+    int wanted_wg = 0;  // ranked variants: workgroups the problem must yield (0: the selection's default for the rank)
 };
 
 const GemmVariant *gemm_variants(int kind, int *count);

@@ -291,7 +291,7 @@ def test_dispatch_plan_is_host_logic(L):
     fully connected configuration the depth-split-across-lanes kernel, many shallow rows the tiled kernel with a low
     tile, few tiles with a long depth the depth ranges, gemm_tbn with few ternary rows the swapped roles."""
     d = binding.lb_describe_plan
-    assert d("tnn", 1024, 50176, 4608) == "tnn tiled kernel [KIND_TNN ts8 tv4 w4 kg4 sg2], A on the scalar side"
+    assert d("tnn", 1024, 50176, 4608) == "tnn tiled kernel [KIND_TNN ts4 tv2 w8 kg8 sg4], A on the scalar side"
     assert d("tnn", 64, 256, 576) == "tnn tiled kernel [KIND_TNN ts1 tv1 w8 kg16 sg4], A on the scalar side"
     assert d("bnn", 256, 3136, 1152) == "bnn tiled kernel [KIND_BNN ts4 tv1 w8 kg16 sg8], A on the scalar side"
     assert d("tbn", 512, 784, 2304) == "tbn tiled kernel [KIND_TBN ts4 tv1 w8 kg16 sg8], B on the scalar side"
