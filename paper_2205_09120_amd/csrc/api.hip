@@ -144,7 +144,12 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
 // (six per compute unit for the 32 x 64 tile of rank 2, eight for the larger tiles), and failing that the ranked
 // variant with the most workgroups.  A scalar side of at most 8 (16) strings only admits tiles of at most 8 (16)
 // rows, so that no wave multiplies padding.
-int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV, int64_t KW)
+// base_only: leave out the instances with conditions of their own (eight waves on a 32 x 128 tile), which were tuned
+// on plain products.  conv_gemm: a thread pays the gather's bounds check and address once per stage, and those
+// instances stage half as many words per thread (headline layer: 745 us with the 32 x 256 tile of four waves, 787 us
+// with them).  gemm_requant: 755 against 774 us on the same layer.
+int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV, int64_t KW,
+                   bool base_only = false)
 {
     const int max_tile_s = rowsS <= 8 ? 8 : rowsS <= 16 ? 16 : 1 << 30;
     const int64_t n16 = ((rowsS + 15) / 16) * ((rowsV + 63) / 64);
@@ -154,7 +159,8 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
     int best = -1, fallback = -1;
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
-        if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s || KW < tab[i].small_min_kw)
+        if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s || KW < tab[i].small_min_kw ||
+            (base_only && tab[i].wanted_wg > 0))
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
         const int64_t wanted = tab[i].wanted_wg > 0 ? tab[i].wanted_wg : tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
@@ -814,7 +820,7 @@ int gemm_requant(int kind, int out_planes, int64_t M, int64_t N, int64_t K, cons
     a.q_out = Out;
     a.q_planes = out_planes;
     const int fv = forced_variant(kind);
-    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
+    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW, true);
     if (const int rc_dev = check_device(name))
         return rc_dev;
     const hipError_t e = tab[v].launch_transposed(a);
@@ -924,7 +930,7 @@ int conv_gemm(int kind, int64_t M, const uint64_t *Ap, const uint64_t *Fp, int64
     a.ldc = ldc;
     a.stream = static_cast<hipStream_t>(stream);
     const int fv = forced_variant(kind);
-    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW);
+    const int v = (fv >= 0 && fv < count) ? fv : choose_variant(tab, count, a.rowsS, a.rowsV, a.KW, true);
     const hipError_t e = tab[v].launch_conv(a, g);
     if (e != hipSuccess)
         return fail(LB_EHIP, "%s: %s", name, hipGetErrorString(e));
