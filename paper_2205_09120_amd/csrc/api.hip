@@ -164,7 +164,10 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
         const int64_t wanted = tab[i].wanted_wg > 0 ? tab[i].wanted_wg : tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
-        if (wg >= wanted && (best < 0 || tab[i].rank > tab[best].rank))
+        // an instance with a threshold of its own is also taken when its workgroups fill whole rounds of two per
+        // compute unit (512 x 4096 x 2304: 512 tiles of 32 x 128, 14 % faster; 576 tiles: 6 % slower)
+        const bool fills = tab[i].wanted_wg > 0 && wg >= 512 && wg % 256 == 0;
+        if ((wg >= wanted || fills) && (best < 0 || tab[i].rank > tab[best].rank))
             best = i;
         if (wg > fallback_wg) {
             fallback_wg = wg;

@@ -857,8 +857,8 @@ const GemmVariant kBnn[] = {
     LB_VARIANT(0, KIND_BNN, 16, 2, 4, 8, 2),
     LB_VARIANT(0, KIND_BNN, 8, 2, 4, 8, 1),
     // 32 x 128 tile with eight waves of four rows (see the ternary table): for products too small for the 64 x 128
-    // tile (512 x 8192 x 2304: 23.9 -> 21.7 us, 512 x 12544 x 2304: 34.6 -> 33.4 us)
-    LB_VARIANT_IF(4, 32, 1024, KIND_BNN, 4, 2, 8, 8, 4),
+    // tile (512 x 8192 x 2304: 23.9 -> 21.7 us, 512 x 4096 x 2304: 15.3 -> 13.1 us, 2048 x 1024 x 4608: 23.9 -> 22.2 us)
+    LB_VARIANT_IF(4, 32, 600, KIND_BNN, 4, 2, 8, 8, 4),
     LB_SMALL(64, 0, KIND_BNN, 1, 1, 4, 16, 8),
     LB_SMALL(160, 0, KIND_BNN, 1, 1, 8, 16, 8),
     LB_SMALL(300, 18, KIND_BNN, 1, 1, 8, 16, 8),
@@ -877,14 +877,17 @@ const GemmVariant kTnn[] = {
     // its SIMDs fed on its own when the launch drains and fewer of them are resident; half the accumulators per wave.
     // Measured against the instances above: 1024 x 50176 x 4608 726 -> 719 us, 1024 x 12544 x 4608 203 -> 196 us,
     // 512 x 12544 x 2304 61 -> 59 us; shallow products (18 depth words: three stages of 8, 8, 2) are slower with it.
-    LB_VARIANT_IF(5, 32, 1024, KIND_TNN, 4, 2, 8, 8, 4),
+    LB_VARIANT_IF(6, 32, 1024, KIND_TNN, 4, 2, 8, 8, 4),
+    // the same on a 32 x 64 tile, for products that yield fewer than 1024 of the tiles above (1024 x 3136 x 9216:
+    // 130 -> 116 us, 512 x 6272 x 4608: 67.5 -> 61.2 us, 384 x 6272 x 3456: 40.1 -> 36.0 us)
+    LB_VARIANT_IF(5, 32, 1024, KIND_TNN, 4, 1, 8, 16, 4),
     LB_SMALL(300, 0, KIND_TNN, 1, 1, 8, 16, 4),
     LB_SMALL(600, 0, KIND_TNN, 2, 1, 8, 16, 4),
     LB_SMALL(1200, 0, KIND_TNN, 4, 1, 8, 16, 4),
 };
 const GemmVariant kTbn[] = {
     LB_VARIANT(1, KIND_TBN, 4, 1, 4, 16, 8),
-    LB_VARIANT(2, KIND_TBN, 8, 1, 4, 8, 4),
+    LB_VARIANT_IF(2, 0, 1024, KIND_TBN, 8, 1, 4, 8, 4),  // from 1024 tiles (384 x 6272 x 3456: 27.6 -> 24.5 us)
     LB_VARIANT_IF(3, 0, 1024, KIND_TBN, 8, 2, 8, 8, 4),  // eight waves: half the workgroups of a four-wave tile fill the device
     LB_VARIANT(4, KIND_TBN, 8, 4, 8, 4, 1),
     LB_VARIANT(0, KIND_TBN, 8, 4, 4, 4, 4),
