@@ -322,6 +322,26 @@ def test_dispatch_plan_is_host_logic(L):
         L.lb_set_variant(1, -1)
 
 
+def test_eight_wave_tiles_are_chosen_by_depth_and_tile_count(L):
+    """The 32 x 128 / 32 x 64 tiles of eight waves: from 32 depth words on, from about a thousand workgroups on, or
+    when their workgroups fill whole rounds of two per compute unit; never for shallow products."""
+    d = binding.lb_describe_plan
+    wide, narrow = "ts4 tv2 w8 kg8 sg4", "ts4 tv1 w8 kg16 sg4"
+    assert wide in d("tnn", 512, 8192, 2304)          # 16 x 64 = 1024 tiles of 32 x 128
+    assert wide in d("tnn", 1024, 12544, 4608)
+    assert narrow in d("tnn", 1024, 3136, 9216)       # 800 tiles of 32 x 128, but 1568 of 32 x 64
+    assert narrow in d("tnn", 384, 6272, 3456)
+    assert wide in d("tnn", 512, 4096, 2304)          # 512 tiles of 32 x 128: exactly two per compute unit
+    assert wide not in d("tnn", 2048, 6272, 1152) and narrow not in d("tnn", 2048, 6272, 1152)   # 18 depth words
+    assert wide in d("bnn", 512, 8192, 2304) and wide in d("bnn", 512, 4096, 2304)
+    assert wide in d("bnn", 300, 9000, 4096)          # 710 tiles >= 600
+    assert wide not in d("bnn", 1536, 1536, 6144)     # 576 tiles: neither enough nor whole rounds
+    assert "ts8 tv2 w8 kg8 sg4" in d("bnn", 1024, 50176, 4608)   # the 64 x 128 tile keeps the largest problems
+    assert "ts8 tv2 w8 kg8 sg4" in d("tbn", 1024, 12544, 4608)   # ternary-binary: eight waves of eight rows from 1024 tiles
+    assert "ts8 tv4 w8 kg4 sg1" in d("tbn", 1024, 50176, 4608)
+    assert "ts8 tv1 w4 kg8 sg4" in d("tbn", 384, 6272, 3456)     # 1176 tiles of 32 x 64
+
+
 def test_grouped_static_argument_validation(L):
     """The allocation-free grouped launch checks its table on the host before any HIP call."""
     P = binding.GemmProblem
