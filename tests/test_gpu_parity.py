@@ -270,6 +270,33 @@ def test_gemm_ldc_and_untouched_padding(kind):
     assert np.all(got[:, N:] == -777)
 
 
+EIGHT_WAVE_SHAPES = [  # (M, N, K, part of the plan the shape-based dispatch must name)
+    ("tnn", 515, 8200, 2304, "ts4 tv2 w8 kg8 sg4"),    # ragged rows and columns, 17 x 65 tiles of 32 x 128
+    ("tnn", 1000, 4100, 2100, "ts4 tv2 w8 kg8 sg4"),   # depth not a multiple of 64
+    ("tnn", 1000, 3100, 2400, "ts4 tv1 w8 kg16 sg4"),  # fewer than 1024 wide tiles: the 32 x 64 tile of eight waves
+    ("bnn", 515, 8200, 2304, "ts4 tv2 w8 kg8 sg4"),
+    ("bnn", 512, 4096, 2112, "ts4 tv2 w8 kg8 sg4"),    # exactly two workgroups per compute unit
+    ("tbn", 2060, 4100, 2100, "ts8 tv2 w8 kg8 sg4"),   # lanes own rows of C: results leave through LDS, written through
+    ("tbn", 515, 8200, 2304, "ts8 tv1 w4 kg8 sg4"),
+    ("tnn", 70000, 13, 300, "B on the scalar side"),   # narrow N: same store path from the 16-row tile
+]
+
+
+@pytest.mark.parametrize("kind,M,N,K,plan", EIGHT_WAVE_SHAPES)
+def test_gemm_eight_wave_tiles_and_row_wise_stores(kind, M, N, K, plan):
+    """The instances the dispatch takes for a thousand tiles and more, at ragged extents, with ldc > N."""
+    got_plan = lb.lb_describe_plan(kind, M, N, K)
+    say(f"gemm_{kind} M={M} N={N} K={K}: {got_plan}")
+    assert plan in got_plan
+    A, B = synth.make_custom(kind, M, N, K, seed=M + N + K)
+    ldc = N + 5
+    C = torch.full((M, ldc), -777, dtype=torch.int32, device="cuda")
+    run_gemm(kind, A, B, C=C, ldc=ldc)
+    got = C.cpu().numpy()
+    assert np.array_equal(got[:, :N], oracle.gemm(A, B))
+    assert np.all(got[:, N:] == -777)
+
+
 def test_same_no_zero_matrix_through_all_three_entry_points():
     """A ternary matrix without zeros is also a binary matrix: the three entry points must agree on it."""
     say("cross-check tnn/tbn/bnn on +-1 matrices")
