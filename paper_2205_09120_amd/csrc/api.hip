@@ -144,8 +144,8 @@ int do_pack(bool ternary, const char *name, const int8_t *src, int64_t rows, int
 // (six per compute unit for the 32 x 64 tile of rank 2, eight for the larger tiles), and failing that the ranked
 // variant with the most workgroups.  A scalar side of at most 8 (16) strings only admits tiles of at most 8 (16)
 // rows, so that no wave multiplies padding.
-// base_only: leave out the instances with conditions of their own (eight waves on a 32 x 128 tile), which were tuned
-// on plain products.  conv_gemm: a thread pays the gather's bounds check and address once per stage, and those
+// base_only: leave out the instances that ask for a minimum depth (eight waves of four rows on a 32 x 128 or 32 x 64
+// tile), which were tuned on plain products.  conv_gemm: a thread pays the gather's bounds check and address once per stage, and those
 // instances stage half as many words per thread (headline layer: 745 us with the 32 x 256 tile of four waves, 787 us
 // with them).  gemm_requant: 755 against 774 us on the same layer.
 int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int64_t rowsV, int64_t KW,
@@ -160,7 +160,7 @@ int choose_variant(const lowbit::GemmVariant *tab, int count, int64_t rowsS, int
     int64_t fallback_wg = -1;
     for (int i = 0; i < count; ++i) {
         if (tab[i].rank <= 0 || tab[i].tileS > max_tile_s || KW < tab[i].small_min_kw ||
-            (base_only && tab[i].wanted_wg > 0))
+            (base_only && tab[i].wanted_wg > 0 && tab[i].small_min_kw > 0))
             continue;
         const int64_t wg = ((rowsS + tab[i].tileS - 1) / tab[i].tileS) * ((rowsV + tab[i].tileV - 1) / tab[i].tileV);
         const int64_t wanted = tab[i].wanted_wg > 0 ? tab[i].wanted_wg : tab[i].rank <= 2 ? 256 * 6 : 256 * 8;
